@@ -1,0 +1,119 @@
+"""Pins for the oracle's aggregated attention score (Section 2.4 Eq. (1); Section 4.2
+Eq. (7); Algorithm 2 step 2).  CPU only.  Each pin is something other than the oracle's
+own formula: a closed form, an invariant, a hand-computed example, or a brute-force
+n x n map built with a library softmax."""
+import math
+
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from oracle import ref
+from paper_2407_08454_amd import synth
+
+
+def _rand(shape, dtype, seed):
+    rng = np.random.default_rng(seed)
+    return synth.to_storage(rng.standard_normal(shape, dtype=np.float32), dtype)
+
+
+def _brute(Q, K, dtype):
+    """Materialised causal map per head: library softmax over an explicitly masked score matrix."""
+    q = synth.to_f64(Q, dtype)
+    k = synth.to_f64(K, dtype)
+    n, d = k.shape
+    s = q @ k.T / math.sqrt(d)
+    s[np.triu(np.ones((n, n), dtype=bool), 1)] = -np.inf
+    return softmax(s, axis=1).sum(axis=0)
+
+
+def test_widening_is_exact_for_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint16)
+    want16 = bits.view(np.float16).astype(np.float64)
+    wantbf = synth.bf16_bits_to_f32(bits).astype(np.float64)
+    for b in list(range(0, 65536, 97)) + [0, 1, 0x03FF, 0x0400, 0x7BFF, 0x7C00, 0x8000, 0xFBFF, 0xFC00, 0x7E00]:
+        got = ref.half_to_double(int(b))
+        assert (math.isnan(got) and math.isnan(want16[b])) or got == want16[b]
+        got = ref.bf16_to_double(int(b))
+        assert (math.isnan(got) and math.isnan(wantbf[b])) or got == wantbf[b]
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 64, 200])
+def test_zero_queries_give_harmonic_numbers(n):
+    # uniform rows: A[t][j] = 1/(t+1) for j <= t, so a_j = H_n - H_j
+    K = _rand((1, 1, n, 16), "f32", 1)
+    Q = np.zeros((1, 1, n, 16), np.float32)
+    a = ref.attn_mass(Q, K, "f32")[0, 0]
+    H = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    np.testing.assert_allclose(a, H[n] - H[:n], rtol=1e-13)
+
+
+def test_identical_keys_give_harmonic_numbers():
+    n, d = 50, 8
+    K = np.tile(_rand((1, 1, 1, d), "f32", 2), (1, 1, n, 1))
+    Q = _rand((1, 1, n, d), "f32", 3)
+    a = ref.attn_mass(Q, K, "f32")[0, 0]
+    H = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    np.testing.assert_allclose(a, H[n] - H[:n], rtol=1e-12)
+
+
+def test_two_token_example_pins_scale_and_operand_roles():
+    # d = 4: scores of query 1 are x/2 and y/2, so A[1][0] = 1/(1+exp((y-x)/2)).
+    d = 4
+    K = np.zeros((1, 1, 2, d), np.float32)
+    Q = np.zeros((1, 1, 2, d), np.float32)
+    K[0, 0, 0] = [1, 0, 0, 0]
+    K[0, 0, 1] = [0, 2, 0, 0]
+    Q[0, 0, 0] = [5, 5, 5, 5]           # row 0 has a single key: irrelevant
+    Q[0, 0, 1] = [3, -1, 7, 7]          # x = q1.k0 = 3, y = q1.k1 = -2
+    a = ref.attn_mass(Q, K, "f32")[0, 0]
+    a10 = 1.0 / (1.0 + math.exp((-2.0 - 3.0) / 2.0))
+    assert a[0] == pytest.approx(1.0 + a10, rel=1e-14)
+    assert a[1] == pytest.approx(1.0 - a10, rel=1e-14)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("n", [1, 5, 33, 64])
+def test_matches_brute_force_map(dtype, n):
+    d = 32
+    Q = _rand((2, 3, n, d), dtype, 10 + n)
+    K = _rand((2, 3, n, d), dtype, 20 + n)
+    a = ref.attn_mass(Q, K, dtype)
+    for b in range(2):
+        for h in range(3):
+            np.testing.assert_allclose(a[b, h], _brute(Q[b, h], K[b, h], dtype), rtol=1e-12)
+
+
+def test_invariants_on_the_workload_generator():
+    q, k, v, _ = synth.gen_slice(0, 0, 256, 128, 1, 0.95, "f32")
+    a = ref.attn_mass(q[None], k[None, None], "f32")[0, 0]
+    assert a.sum() == pytest.approx(256.0, rel=1e-12)      # every row of the map sums to 1
+    assert a[0] >= 1.0                                      # row 0 gives all its mass to key 0
+    assert 0.0 < a[-1] <= 1.0                               # the last key is seen by one row only
+    assert (a > 0).all()
+
+
+def test_gqa_is_the_sum_of_the_query_heads():
+    n, d, G = 40, 16, 4
+    K = _rand((1, 2, n, d), "bf16", 5)
+    Q = _rand((1, 2 * G, n, d), "bf16", 6)
+    a = ref.attn_mass(Q, K, "bf16", G=G)
+    for h in range(2):
+        parts = sum(_brute(Q[0, h * G + g], K[0, h], "bf16") for g in range(G))
+        np.testing.assert_allclose(a[0, h], parts, rtol=1e-12)
+        assert a[0, h].sum() == pytest.approx(G * n, rel=1e-12)
+
+
+def test_ragged_lengths_ignore_padding():
+    N, d = 48, 16
+    lens = np.array([48, 17, 0, 1], np.int32)
+    K = _rand((4, 1, N, d), "f16", 7)
+    Q = _rand((4, 1, N, d), "f16", 8)
+    for b, n in enumerate(lens):   # finite garbage in the padding must not leak
+        K[b, 0, n:] = 1.0e4
+        Q[b, 0, n:] = 1.0e4
+    a = ref.attn_mass(Q, K, "f16", seq_lens=lens)
+    for b, n in enumerate(lens):
+        assert (a[b, 0, n:] == 0).all()
+        if n:
+            np.testing.assert_allclose(a[b, 0, :n], _brute(Q[b, 0, :n], K[b, 0, :n], "f16"), rtol=1e-12)
