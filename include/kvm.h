@@ -1,0 +1,189 @@
+/*
+ * kvm.h -- C ABI of the KV-cache merging compression pass for AMD MI355X (gfx950).
+ *
+ * The pass runs independently over every (batch, KV-head) slice of a prefilled
+ * cache (fold layers into the batch axis) in three calls:
+ *
+ *   kvm_attn_mass      aggregated attention score of every key
+ *   kvm_identify_sets  contiguous merging sets + pivot of each set
+ *   kvm_merge          Gaussian-kernel weighted merge into a compacted cache
+ *
+ * Conventions for every call
+ *   - Every tensor pointer is a DEVICE pointer to contiguous memory, innermost
+ *     axis d; Q is (B, H_kv*G, N, d) with the G query heads of KV head h at
+ *     head indices h*G .. h*G+G-1; K and V are (B, H_kv, N, d).
+ *   - The caller owns every buffer, including the workspace.  The library
+ *     allocates nothing, keeps no state between calls and never synchronises:
+ *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns.  Outputs are valid after the caller
+ *     synchronises the stream.
+ *   - Sequences are right-padded: batch row b has valid tokens [0, n_b),
+ *     n_b = seq_lens[b] (device array of B int32; values are clamped to
+ *     [0, N]) or N when seq_lens is NULL.  Padded positions are never read as
+ *     data.
+ *   - Errors are return codes; nothing throws or aborts.  Host-detectable
+ *     errors (null pointer, unsupported shape, small workspace) return before
+ *     any launch and leave outputs untouched; kvm_last_error() then holds a
+ *     message.  Data-dependent per-slice conditions are reported on the device
+ *     in slice_status and the call still returns KVM_OK.
+ *   - v1 limits: d == 128; G >= 1; N >= 0; dtype one of kvm_dtype.
+ */
+#ifndef KVM_H
+#define KVM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { KVM_F32 = 0, KVM_F16 = 1, KVM_BF16 = 2 } kvm_dtype;
+
+typedef enum {
+    KVM_OK = 0,
+    KVM_ERR_INVALID_ARG = 1,  /* null pointer, negative size, ratio outside [0,1], ...      */
+    KVM_ERR_UNSUPPORTED = 2,  /* d != 128, unknown dtype or sigma mode                      */
+    KVM_ERR_WORKSPACE = 3,    /* ws == NULL or ws_bytes < kvm_workspace_bytes()             */
+    KVM_ERR_LAUNCH = 4        /* the HIP runtime refused a launch; see kvm_last_error()     */
+} kvm_status;
+
+/* Bits of slice_status[b,h] written by kvm_identify_sets. */
+enum {
+    KVM_SLICE_FALLBACK = 1,   /* the budget fallback removed at least one boundary          */
+    KVM_SLICE_INFEASIBLE = 2, /* even with every removable boundary gone M > floor(budget n) */
+    KVM_SLICE_TRUNCATED = 4   /* M > capacity: only the first `capacity` sets were stored   */
+};
+
+typedef enum {
+    KVM_SIGMA_MEAN_DIST = 0,  /* sigma = (sum of distances to the pivot) / (sqrt(2) |S|)     */
+    KVM_SIGMA_FIXED = 1       /* sigma given by the caller (the fixed-sigma study, Sec. 5.4) */
+} kvm_sigma_mode;
+
+typedef struct {
+    int32_t B;                /* batch (x layers): every (b, h) slice is independent         */
+    int32_t H_kv;             /* KV heads                                                     */
+    int32_t G;                /* query heads per KV head (1, or e.g. 4 for grouped queries)   */
+    int32_t N;                /* padded sequence length                                       */
+    int32_t d;                /* head dimension (128)                                         */
+    int32_t dtype;            /* kvm_dtype of Q, K, V and of K_out, V_out                     */
+    const int32_t *seq_lens;  /* DEVICE pointer [B], or NULL when every length is N           */
+} kvm_shape;
+
+typedef struct {
+    double budget;            /* beta: a slice may keep floor(beta n_b) states                */
+    double recent_ratio;      /* the last floor(r n_b) tokens are conserved                   */
+    double heavy_ratio;       /* the floor(r n_b) largest scores among the others are too     */
+    float threshold;          /* epsilon: neighbours merge iff cosine similarity > epsilon    */
+    int32_t sigma_mode;       /* kvm_sigma_mode                                               */
+    float sigma;              /* used when sigma_mode == KVM_SIGMA_FIXED (must be > 0)        */
+    int32_t value_scale_by_set_size; /* 1: value weights are |S| w_i (Sec. 4.2); 0: w_i      */
+    int32_t enforce_budget;   /* 1: remove boundaries until M <= floor(beta n_b) (see below)  */
+} kvm_params;
+
+/*
+ * The two scenarios of Section 5.1 ("Implementation details"): budget 0.50 ->
+ * recent 0.17, heavy 0.12; budget 0.35 -> recent 0.08, heavy 0.02; threshold
+ * 0.75 for both (the proportions are read as fractions of the length).  Other
+ * budgets in (0,1] get recent = 0.34 beta, heavy = 0.24 beta (the 0.50 row
+ * scaled).  Sets sigma_mode = MEAN_DIST, value_scale_by_set_size = 1,
+ * enforce_budget = 1.  Host call.  KVM_ERR_INVALID_ARG if out == NULL or budget
+ * is not in (0,1].
+ */
+kvm_status kvm_params_for_budget(double budget, kvm_params *out);
+
+/*
+ * Rows per slice of set_start (+1), pivot, K_out and V_out:
+ * floor(budget * N) when enforce_budget is set, else N.  Host call; returns -1
+ * on invalid arguments.
+ */
+int32_t kvm_out_capacity(const kvm_shape *shape, const kvm_params *params);
+
+/*
+ * Bytes of device workspace that is enough for any of the three calls on this
+ * shape (256-byte aligned pointer expected).  Host call; 0 on invalid
+ * arguments.  Contents need no initialisation and are not preserved.
+ */
+size_t kvm_workspace_bytes(const kvm_shape *shape, const kvm_params *params);
+
+/*
+ * Aggregated attention score (Section 2.4 Eq. (1); Section 4.2 Eq. (7);
+ * Algorithm 2 step 2):
+ *     A_g = causal softmax(Q_g K^T / sqrt(d)) per query head g of the KV head,
+ *     mass[b,h,j] = sum over g and over query rows t >= j of A_g[t,j].
+ * With G > 1 the per-head maps are summed (the paper averages them for grouped
+ * queries, Section 5.2: the same up to the factor G).
+ *   Q     in   (B, H_kv*G, N, d) dtype
+ *   K     in   (B, H_kv, N, d)   dtype
+ *   mass  out  (B, H_kv, N) float32; 0 at positions >= n_b
+ * Scores are accumulated in fp32 from the stored inputs; the map is never
+ * materialised.  Deterministic (no atomics).
+ */
+kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, float *mass,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Merging-set identification (Section 3.2; Section 4.1 Def. 4.1 and Algorithm 1;
+ * conserved states: Section 4.1 last paragraph and Section 5.1; pivot: Eq. (7)).
+ * Per slice, with n = n_b:
+ *   1. conserved tokens: the last floor(recent_ratio n), plus the
+ *      floor(heavy_ratio n) largest `mass` among the others (ties: lower index);
+ *   2. sim[j] = cosine similarity of k_{j-1} and k_j (Eq. (2)), 0 if a norm is 0;
+ *   3. token j-1 and j share a set iff sim[j] > threshold and neither is
+ *      conserved (Algorithm 1 read as a chain of adjacent tokens); sets are
+ *      therefore contiguous, disjoint and cover [0, n); conserved tokens are
+ *      singletons;
+ *   4. if enforce_budget and the number of sets M > floor(budget n): the
+ *      M - floor(budget n) boundaries between two non-conserved tokens with the
+ *      largest sim are removed (ties: higher index first), i.e. the slice's
+ *      threshold is lowered just enough; if there are not enough of them all are
+ *      removed and KVM_SLICE_INFEASIBLE is set;
+ *   5. pivot of a set = its token with the largest mass (ties: lowest index).
+ *   K            in   (B, H_kv, N, d)
+ *   mass         in   (B, H_kv, N) float32 (finite; as written by kvm_attn_mass)
+ *   set_id       out  (B, H_kv, N) int32: set of token j, -1 at positions >= n
+ *   set_start    out  (B, H_kv, capacity+1) int32: first token of set s for
+ *                     s < M (s <= capacity); remaining entries hold n
+ *   pivot        out  (B, H_kv, capacity) int32: absolute position; -1 for s >= M
+ *   n_sets       out  (B, H_kv) int32: M (may exceed capacity: KVM_SLICE_TRUNCATED)
+ *   sim_opt      out  (B, H_kv, N) float32 or NULL; sim[0] and padding are 0
+ *   slice_status out  (B, H_kv) int32: KVM_SLICE_* bits
+ * capacity = kvm_out_capacity().  Sets are numbered in sequence order, so the
+ * compacted cache stays position-ordered.  Integer outputs are deterministic.
+ */
+kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, const void *K,
+                             const float *mass, int32_t *set_id, int32_t *set_start, int32_t *pivot,
+                             int32_t *n_sets, float *sim_opt, int32_t *slice_status, void *ws,
+                             size_t ws_bytes, void *stream);
+
+/*
+ * Gaussian-kernel weighted merging (Section 4.2: Def. 4.2 Eq. (4), Eq. (5), (6);
+ * Algorithm 2).  For every stored set S with pivot p:
+ *     D_j = ||k_p - k_j||_2,  g_j = exp(-D_j^2 / (2 sigma^2)),  w_j = g_j / sum g,
+ *     K_out[s] = sum w_j k_j,   V_out[s] = c sum w_j v_j,  c = |S| or 1.
+ * sigma: KVM_SIGMA_MEAN_DIST -> sum_j D_j / (sqrt(2) |S|) (all g = 1 when it is
+ * 0, so a singleton is copied bit for bit); KVM_SIGMA_FIXED -> params->sigma.
+ *   K, V        in   (B, H_kv, N, d)
+ *   set_start, pivot, n_sets  in   as written by kvm_identify_sets (entries are
+ *               clamped to the slice, so inconsistent maps cannot cause
+ *               out-of-range accesses)
+ *   K_out,V_out out  (B, H_kv, capacity, d) dtype; row s < min(M, capacity) is
+ *               set s; other rows are not written.  fp32 accumulation, one
+ *               round-to-nearest-even to dtype.
+ *   w_opt       out  (B, H_kv, N) float32 or NULL: key weight of every token
+ *               (positions not covered by a stored set are not written)
+ */
+kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                     const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,
+                     void *K_out, void *V_out, float *w_opt, void *ws, size_t ws_bytes, void *stream);
+
+/* Message of the calling thread's last failed call ("" if none).  Static storage. */
+const char *kvm_last_error(void);
+
+/* Library version, "major.minor.patch". */
+const char *kvm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVM_H */

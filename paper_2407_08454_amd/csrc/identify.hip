@@ -1,0 +1,459 @@
+// Merging-set identification (Section 3.2; Section 4.1 Def. 4.1 and Algorithm 1;
+// conserved states: Section 4.1 last paragraph, Section 5.1; pivot: Section 4.2 Eq. (7)).
+//
+// Two kernels:
+//   cosine_scan_kernel  streams K once and writes sim[j] = cos(k_{j-1}, k_j) (Eq. (2));
+//                       HBM-bound, 16 lanes per 128-wide row, 16 B per lane.
+//   segment_kernel      one workgroup per slice: exact top-k of the aggregated scores by
+//                       radix select, boundary flags, prefix scan to set ids, the budget
+//                       fallback, and a segmented arg-max scan for the pivots.  All integer
+//                       outputs are deterministic.
+#include "kvm_common.h"
+
+namespace kvm {
+
+// ------------------------------------------------------------------------------------------
+// cosine scan
+// ------------------------------------------------------------------------------------------
+
+constexpr int COS_BLOCK = 256;
+constexpr int COS_ROWS_PER_GROUP = 16;                      // consecutive rows per 16-lane group
+constexpr int COS_ROWS_PER_BLOCK = (COS_BLOCK / 16) * COS_ROWS_PER_GROUP;
+constexpr int COS_BATCH = 8;                                 // rows in flight per group
+
+template <typename T>
+__global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restrict__ K, float *__restrict__ sim,
+                                                                 const int32_t *__restrict__ seq_lens, int H, int N,
+                                                                 int tiles_per_slice)
+{
+    const int slice = blockIdx.x / tiles_per_slice;
+    const int tile = blockIdx.x - slice * tiles_per_slice;
+    const int n = clamp_len(seq_lens, slice / H, N);
+    const int c = threadIdx.x & 15;
+    const int j0 = tile * COS_ROWS_PER_BLOCK + (threadIdx.x >> 4) * COS_ROWS_PER_GROUP;
+    if (j0 >= N) return;
+    const T *Ks = K + (size_t)slice * N * HEAD_DIM;
+    float *sims = sim + (size_t)slice * N;
+
+    float prev[8];
+    float nprev = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) prev[i] = 0.f;
+    if (j0 >= 1 && j0 - 1 < n) {
+        Elem<T>::to_float(Elem<T>::load(Ks + (size_t)(j0 - 1) * HEAD_DIM, c), prev);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s = fmaf(prev[i], prev[i], s);
+        nprev = row16_sum(s);
+    }
+#pragma unroll
+    for (int base = 0; base < COS_ROWS_PER_GROUP; base += COS_BATCH) {
+        typename Elem<T>::Raw raw[COS_BATCH];
+#pragma unroll
+        for (int i = 0; i < COS_BATCH; ++i) {
+            const int j = j0 + base + i;
+            if (j < n) raw[i] = Elem<T>::load(Ks + (size_t)j * HEAD_DIM, c);
+        }
+#pragma unroll
+        for (int i = 0; i < COS_BATCH; ++i) {
+            const int j = j0 + base + i;
+            if (j >= N) break;
+            if (j >= n) {                                    // padding: defined, never read as data
+                if (c == 0) sims[j] = 0.f;
+                continue;
+            }
+            float cur[8];
+            Elem<T>::to_float(raw[i], cur);
+            float dot = 0.f, nn = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                dot = fmaf(cur[e], prev[e], dot);
+                nn = fmaf(cur[e], cur[e], nn);
+            }
+            dot = row16_sum(dot);
+            nn = row16_sum(nn);
+            float s = 0.f;                                   // zero norm or first token: similarity 0
+            if (j > 0 && nn > 0.f && nprev > 0.f) s = dot / (sqrtf(nn) * sqrtf(nprev));
+            if (c == 0) sims[j] = s;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) prev[e] = cur[e];
+            nprev = nn;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// segmentation: one workgroup per slice
+// ------------------------------------------------------------------------------------------
+
+constexpr int SEG_BLOCK = 1024;
+constexpr int SEG_WAVES = SEG_BLOCK / WAVE;
+constexpr int SEG_ITEMS = 4;
+constexpr int SEG_TILE = SEG_BLOCK * SEG_ITEMS;
+
+struct SegShared {
+    int hist[256];
+    int wave_i[SEG_WAVES];
+    int wave_i2[SEG_WAVES];
+    unsigned long long wave_k[SEG_WAVES];
+    int wave_f[SEG_WAVES];
+    int bc[4];
+    unsigned long long bck;
+};
+
+__device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long v, int off) {
+    uint32_t lo = __shfl_up((uint32_t)v, off, WAVE), hi = __shfl_up((uint32_t)(v >> 32), off, WAVE);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// Exclusive prefix sum of one int per thread over the block; total returned to all threads.
+__device__ __forceinline__ int block_exclusive_sum(int v, int &total, int *wave_slots) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        int t = __shfl_up(inc, off, WAVE);
+        if (lane >= off) inc += t;
+    }
+    __syncthreads();                                         // wave_slots may still be read from a previous use
+    if (lane == WAVE - 1) wave_slots[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < SEG_WAVES; ++i) {
+        int a = wave_slots[i];
+        if (i < w) before += a;
+        all += a;
+    }
+    total = all;
+    return before + inc - v;
+}
+
+__device__ __forceinline__ int block_sum(int v, int *wave_slots) {
+    int total;
+    (void)block_exclusive_sum(v, total, wave_slots);
+    return total;
+}
+
+// k-th largest (k >= 1) of the keys that `key_at(j, key)` accepts for j in [0, count).
+// Needs k <= number of accepted keys.  Returns the key value T and the number of accepted
+// keys strictly greater than T.  MSB-first radix select, 8 bits per pass.
+template <typename KeyFn>
+__device__ void block_select_kth_largest(KeyFn key_at, int count, int k, uint32_t &T, int &greater, SegShared &sh)
+{
+    uint32_t prefix = 0, mask = 0;
+    int remaining = k, gt = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int i = threadIdx.x; i < 256; i += SEG_BLOCK) sh.hist[i] = 0;
+        __syncthreads();
+        for (int j = threadIdx.x; j < count; j += SEG_BLOCK) {
+            uint32_t key;
+            if (key_at(j, key) && (key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (threadIdx.x < WAVE) {
+            const int lane = threadIdx.x;
+            int h[4], s = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { h[i] = sh.hist[lane * 4 + i]; s += h[i]; }
+            int suf = s;                                     // inclusive suffix sum over lanes
+#pragma unroll
+            for (int off = 1; off < WAVE; off <<= 1) {
+                int t = __shfl_down(suf, off, WAVE);
+                if (lane + off < WAVE) suf += t;
+            }
+            int above = suf - s;                             // keys in higher-numbered lanes' bins
+#pragma unroll
+            for (int i = 3; i >= 0; --i) {
+                if (above < remaining && remaining <= above + h[i]) { sh.bc[0] = lane * 4 + i; sh.bc[1] = above; }
+                above += h[i];
+            }
+        }
+        __syncthreads();
+        const int digit = sh.bc[0], above = sh.bc[1];
+        gt += above;
+        remaining -= above;
+        prefix |= (uint32_t)digit << shift;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    T = prefix;
+    greater = gt;
+}
+
+struct SegArgs {
+    const float *mass;
+    const float *sim;
+    uint8_t *flags;
+    int32_t *set_id, *set_start, *pivot, *n_sets, *slice_status;
+    const int32_t *seq_lens;
+    int H, N, cap_rows, enforce;
+    double budget, recent_ratio, heavy_ratio;
+    float threshold;
+};
+
+__global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
+{
+    __shared__ SegShared sh;
+    const int slice = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int n = clamp_len(a.seq_lens, slice / a.H, a.N);
+    const float *mass = a.mass + (size_t)slice * a.N;
+    const float *sim = a.sim + (size_t)slice * a.N;
+    uint8_t *flags = a.flags + (size_t)slice * a.N;
+    int32_t *set_id = a.set_id + (size_t)slice * a.N;
+    int32_t *set_start = a.set_start + (size_t)slice * (a.cap_rows + 1);
+    int32_t *pivot = a.pivot + (size_t)slice * a.cap_rows;
+    const float eps = a.threshold;
+
+    int n_recent = (int)floor(a.recent_ratio * (double)n);
+    if (n_recent > n) n_recent = n;
+    int n_heavy = (int)floor(a.heavy_ratio * (double)n);
+    const int pre = n - n_recent;                            // the top-k is taken over [0, pre)
+    if (n_heavy > pre) n_heavy = pre;
+    const int cap = (int)floor(a.budget * (double)n);
+
+    for (int j = n + tid; j < a.N; j += SEG_BLOCK) set_id[j] = -1;
+
+    // ---- conserved tokens: recent window + exact top-k of mass (ties: lower index) ----------
+    uint32_t T1 = 0;
+    int take_eq1 = 0;
+    if (n_heavy > 0) {
+        int gt1;
+        block_select_kth_largest([&](int j, uint32_t &key) { key = sortable_key(mass[j]); return true; }, pre,
+                                 n_heavy, T1, gt1, sh);
+        take_eq1 = n_heavy - gt1;
+    }
+    {
+        int carry = 0;
+        for (int t0 = 0; t0 < n; t0 += SEG_TILE) {
+            const int jb = t0 + tid * SEG_ITEMS;
+            uint32_t key[SEG_ITEMS];
+            int eq_cnt = 0;
+#pragma unroll
+            for (int i = 0; i < SEG_ITEMS; ++i) {
+                const int j = jb + i;
+                key[i] = (j < pre && n_heavy > 0) ? sortable_key(mass[j]) : 0u;
+                if (j < pre && n_heavy > 0 && key[i] == T1) ++eq_cnt;
+            }
+            int total;
+            int rank = carry + block_exclusive_sum(eq_cnt, total, sh.wave_i);
+#pragma unroll
+            for (int i = 0; i < SEG_ITEMS; ++i) {
+                const int j = jb + i;
+                if (j >= n) break;
+                bool prot = j >= pre;
+                if (!prot && n_heavy > 0) {
+                    if (key[i] > T1) prot = true;
+                    else if (key[i] == T1) { prot = rank < take_eq1; ++rank; }
+                }
+                flags[j] = prot ? 1 : 0;
+            }
+            carry += total;
+        }
+    }
+    __syncthreads();
+
+    // j-1 and j may share a set (before the budget rule); "natural" boundary = both free, sim <= eps
+    auto joins = [&](int j) -> bool { return j >= 1 && !(flags[j] & 1) && !(flags[j - 1] & 1) && sim[j] > eps; };
+    auto natural = [&](int j) -> bool { return j >= 1 && !(flags[j] & 1) && !(flags[j - 1] & 1) && !(sim[j] > eps); };
+
+    // ---- count sets and natural boundaries ----------------------------------------------------
+    int m0 = 0, nat = 0;
+    for (int j = tid; j < n; j += SEG_BLOCK) {
+        m0 += joins(j) ? 0 : 1;
+        nat += natural(j) ? 1 : 0;
+    }
+    const int M0 = block_sum(m0, sh.wave_i);
+    const int n_nat = block_sum(nat, sh.wave_i2);
+    int status = 0;
+
+    // ---- budget fallback: remove the most similar natural boundaries (ties: higher index) -----
+    if (a.enforce && M0 > cap) {
+        const int r = M0 - cap;
+        bool all = n_nat <= r;
+        uint32_t T2 = 0;
+        int take_eq2 = 0, total_eq2 = 0;
+        if (n_nat < r) status |= KVM_SLICE_INFEASIBLE;
+        if (n_nat > 0) status |= KVM_SLICE_FALLBACK;
+        if (!all) {
+            int gt2;
+            block_select_kth_largest([&](int j, uint32_t &key) { key = sortable_key(sim[j]); return natural(j); }, n, r,
+                                     T2, gt2, sh);
+            take_eq2 = r - gt2;
+            int eqc = 0;
+            for (int j = tid; j < n; j += SEG_BLOCK) eqc += (natural(j) && sortable_key(sim[j]) == T2) ? 1 : 0;
+            total_eq2 = block_sum(eqc, sh.wave_i);
+        }
+        if (n_nat > 0) {
+            int carry = 0;
+            for (int t0 = 0; t0 < n; t0 += SEG_TILE) {
+                const int jb = t0 + tid * SEG_ITEMS;
+                bool isnat[SEG_ITEMS];
+                uint32_t key[SEG_ITEMS];
+                int eq_cnt = 0;
+#pragma unroll
+                for (int i = 0; i < SEG_ITEMS; ++i) {
+                    const int j = jb + i;
+                    isnat[i] = j < n && natural(j);
+                    key[i] = isnat[i] ? sortable_key(sim[j]) : 0u;
+                    if (isnat[i] && !all && key[i] == T2) ++eq_cnt;
+                }
+                int total;
+                int rank = carry + block_exclusive_sum(eq_cnt, total, sh.wave_i2);
+#pragma unroll
+                for (int i = 0; i < SEG_ITEMS; ++i) {
+                    const int j = jb + i;
+                    if (!isnat[i]) continue;
+                    bool rem = all || key[i] > T2;
+                    if (!rem && key[i] == T2) { rem = (total_eq2 - 1 - rank) < take_eq2; ++rank; }
+                    if (rem) flags[j] |= 2;
+                }
+                carry += total;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- set ids, set starts, pivots -------------------------------------------------------------
+    auto head = [&](int j) -> bool { return !(joins(j) || (flags[j] & 2)); };   // j starts a set
+    int set_carry = 0;
+    unsigned long long key_carry = 0;                        // running max of the set that crosses the tile edge
+    for (int t0 = 0; t0 < n; t0 += SEG_TILE) {
+        const int jb = t0 + tid * SEG_ITEMS;
+        bool hd[SEG_ITEMS + 1];
+        unsigned long long key[SEG_ITEMS];
+        int heads = 0;
+#pragma unroll
+        for (int i = 0; i <= SEG_ITEMS; ++i) {
+            const int j = jb + i;
+            hd[i] = j < n ? head(j) : true;                  // the position after the last token closes a set
+            if (i < SEG_ITEMS && j < n) {
+                heads += hd[i] ? 1 : 0;
+                key[i] = ((unsigned long long)sortable_key(mass[j]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+            }
+        }
+        // thread summary for the segmented max scan: (any head, max of the trailing open segment)
+        int f = 0;
+        unsigned long long k = 0;
+#pragma unroll
+        for (int i = 0; i < SEG_ITEMS; ++i) {
+            if (jb + i >= n) break;
+            if (hd[i]) { f = 1; k = key[i]; }
+            else k = k > key[i] ? k : key[i];
+        }
+        int total_heads;
+        const int sets_before = set_carry + block_exclusive_sum(heads, total_heads, sh.wave_i);
+        // inclusive segmented scan over thread summaries within the wave
+        const int lane = tid & 63, w = tid >> 6;
+        int fi = f;
+        unsigned long long ki = k;
+#pragma unroll
+        for (int off = 1; off < WAVE; off <<= 1) {
+            int f2 = __shfl_up(fi, off, WAVE);
+            unsigned long long k2 = shfl_up_u64(ki, off);
+            if (lane >= off) {
+                if (!fi) ki = ki > k2 ? ki : k2;
+                fi |= f2;
+            }
+        }
+        if (lane == WAVE - 1) { sh.wave_f[w] = fi; sh.wave_k[w] = ki; }
+        int fe = __shfl_up(fi, 1, WAVE);                     // exclusive within the wave
+        unsigned long long ke = shfl_up_u64(ki, 1);
+        if (lane == 0) { fe = 0; ke = 0; }
+        __syncthreads();
+        int fp = 0;                                          // everything before this wave, tile carry included
+        unsigned long long kp = key_carry;
+        for (int i = 0; i < w; ++i) {
+            if (sh.wave_f[i]) { fp = 1; kp = sh.wave_k[i]; }
+            else kp = kp > sh.wave_k[i] ? kp : sh.wave_k[i];
+        }
+        unsigned long long incoming = fe ? ke : (kp > ke ? kp : ke);
+        // walk the thread's items
+        int s = sets_before - 1;
+        unsigned long long cur = incoming;
+#pragma unroll
+        for (int i = 0; i < SEG_ITEMS; ++i) {
+            const int j = jb + i;
+            if (j >= n) break;
+            if (hd[i]) {
+                ++s;
+                cur = key[i];
+                if (s <= a.cap_rows) set_start[s] = j;
+            } else {
+                cur = cur > key[i] ? cur : key[i];
+            }
+            set_id[j] = s;
+            if (hd[i + 1] && s < a.cap_rows) pivot[s] = (int32_t)(0xFFFFFFFFu - (uint32_t)cur);
+        }
+        // carry to the next tile: the inclusive value of the last thread
+        __syncthreads();
+        if (tid == SEG_BLOCK - 1) sh.bck = cur;
+        __syncthreads();
+        key_carry = sh.bck;
+        set_carry += total_heads;
+        (void)fp;
+    }
+    const int M = set_carry;
+    for (int s = M + tid; s <= a.cap_rows; s += SEG_BLOCK) {
+        set_start[s] = n;
+        if (s < a.cap_rows) pivot[s] = -1;
+    }
+    if (M > a.cap_rows) status |= KVM_SLICE_TRUNCATED;
+    if (tid == 0) {
+        a.n_sets[slice] = M;
+        a.slice_status[slice] = status;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host launcher
+// ------------------------------------------------------------------------------------------
+
+template <typename T>
+static void launch_cosine(const kvm_shape &sh, const void *K, float *sim, hipStream_t st)
+{
+    const int tiles = (sh.N + COS_ROWS_PER_BLOCK - 1) / COS_ROWS_PER_BLOCK;
+    const long long blocks = (long long)sh.B * sh.H_kv * tiles;
+    hipLaunchKernelGGL(cosine_scan_kernel<T>, dim3((unsigned)blocks), dim3(COS_BLOCK), 0, st, (const T *)K, sim,
+                       sh.seq_lens, sh.H_kv, sh.N, tiles);
+}
+
+kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const float *mass,
+                           int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets, float *sim,
+                           uint8_t *flags, int32_t *slice_status, hipStream_t st)
+{
+    const long long slices = (long long)sh.B * sh.H_kv;
+    if (slices == 0) return KVM_OK;
+    if (sh.N > 0) {
+        switch (sh.dtype) {
+        case KVM_F32: launch_cosine<float>(sh, K, sim, st); break;
+        case KVM_F16: launch_cosine<half_t>(sh, K, sim, st); break;
+        default: launch_cosine<bf16_t>(sh, K, sim, st); break;
+        }
+        kvm_status rc = check_launch("cosine_scan_kernel");
+        if (rc != KVM_OK) return rc;
+    }
+    SegArgs a;
+    a.mass = mass;
+    a.sim = sim;
+    a.flags = flags;
+    a.set_id = set_id;
+    a.set_start = set_start;
+    a.pivot = pivot;
+    a.n_sets = n_sets;
+    a.slice_status = slice_status;
+    a.seq_lens = sh.seq_lens;
+    a.H = sh.H_kv;
+    a.N = sh.N;
+    a.cap_rows = cap_rows;
+    a.enforce = pr.enforce_budget;
+    a.budget = pr.budget;
+    a.recent_ratio = pr.recent_ratio;
+    a.heavy_ratio = pr.heavy_ratio;
+    a.threshold = pr.threshold;
+    hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), 0, st, a);
+    return check_launch("segment_kernel");
+}
+
+}  // namespace kvm

@@ -1,0 +1,196 @@
+// Host side of the C ABI declared in include/kvm.h: argument validation, workspace
+// carving, error strings and kernel dispatch.  No allocation, no synchronisation.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "kvm_common.h"
+
+namespace kvm {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+kvm_status check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: launch failed: %s", what, hipGetErrorString(e));
+        return KVM_ERR_LAUNCH;
+    }
+    return KVM_OK;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static kvm_status check_shape(const kvm_shape *sh, const char *fn)
+{
+    if (!sh) { set_error("%s: shape is NULL", fn); return KVM_ERR_INVALID_ARG; }
+    if (sh->B < 0 || sh->H_kv < 1 || sh->G < 1 || sh->N < 0) {
+        set_error("%s: invalid sizes B=%d H_kv=%d G=%d N=%d", fn, sh->B, sh->H_kv, sh->G, sh->N);
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (sh->d != HEAD_DIM) { set_error("%s: head dimension %d is not supported (only %d)", fn, sh->d, HEAD_DIM); return KVM_ERR_UNSUPPORTED; }
+    if (sh->dtype != KVM_F32 && sh->dtype != KVM_F16 && sh->dtype != KVM_BF16) {
+        set_error("%s: unknown dtype %d", fn, sh->dtype);
+        return KVM_ERR_UNSUPPORTED;
+    }
+    // grids and int32 offsets inside a slice
+    const long long slices = (long long)sh->B * sh->H_kv * sh->G;
+    if (slices > (1ll << 24) || (long long)sh->N > (1ll << 22)) {
+        set_error("%s: shape too large (B*H_kv*G=%lld, N=%d)", fn, slices, sh->N);
+        return KVM_ERR_UNSUPPORTED;
+    }
+    return KVM_OK;
+}
+
+static kvm_status check_params(const kvm_params *pr, const char *fn)
+{
+    if (!pr) { set_error("%s: params is NULL", fn); return KVM_ERR_INVALID_ARG; }
+    const bool ok = pr->budget >= 0.0 && pr->budget <= 1.0 && pr->recent_ratio >= 0.0 && pr->recent_ratio <= 1.0 &&
+                    pr->heavy_ratio >= 0.0 && pr->heavy_ratio <= 1.0;
+    if (!ok) {
+        set_error("%s: budget/recent_ratio/heavy_ratio must lie in [0,1] (%g, %g, %g)", fn, pr->budget,
+                  pr->recent_ratio, pr->heavy_ratio);
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (pr->enforce_budget && pr->recent_ratio + pr->heavy_ratio > pr->budget) {
+        set_error("%s: recent_ratio + heavy_ratio = %g exceeds the budget %g", fn, pr->recent_ratio + pr->heavy_ratio,
+                  pr->budget);
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (!(pr->threshold == pr->threshold)) { set_error("%s: threshold is NaN", fn); return KVM_ERR_INVALID_ARG; }
+    if (pr->sigma_mode != KVM_SIGMA_MEAN_DIST && pr->sigma_mode != KVM_SIGMA_FIXED) {
+        set_error("%s: unknown sigma_mode %d", fn, pr->sigma_mode);
+        return KVM_ERR_UNSUPPORTED;
+    }
+    if (pr->sigma_mode == KVM_SIGMA_FIXED && !(pr->sigma > 0.f)) {
+        set_error("%s: fixed sigma must be > 0 (%g)", fn, (double)pr->sigma);
+        return KVM_ERR_INVALID_ARG;
+    }
+    return KVM_OK;
+}
+
+static int capacity(const kvm_shape *sh, const kvm_params *pr)
+{
+    return pr->enforce_budget ? (int)floor(pr->budget * (double)sh->N) : sh->N;
+}
+
+static size_t ws_attn(const kvm_shape *sh) { return align_up((size_t)sh->B * sh->H_kv * sh->G * sh->N * sizeof(float), 256); }
+static size_t ws_identify(const kvm_shape *sh)
+{
+    const size_t tok = (size_t)sh->B * sh->H_kv * sh->N;
+    return align_up(tok * sizeof(float), 256) + align_up(tok, 256);
+}
+
+}  // namespace kvm
+
+using namespace kvm;
+
+extern "C" {
+
+kvm_status kvm_params_for_budget(double budget, kvm_params *out)
+{
+    if (!out || !(budget > 0.0 && budget <= 1.0)) {
+        set_error("kvm_params_for_budget: need out != NULL and 0 < budget <= 1");
+        return KVM_ERR_INVALID_ARG;
+    }
+    memset(out, 0, sizeof(*out));
+    out->budget = budget;
+    if (budget == 0.5) { out->recent_ratio = 0.17; out->heavy_ratio = 0.12; }
+    else if (budget == 0.35) { out->recent_ratio = 0.08; out->heavy_ratio = 0.02; }
+    else { out->recent_ratio = 0.34 * budget; out->heavy_ratio = 0.24 * budget; }
+    out->threshold = 0.75f;
+    out->sigma_mode = KVM_SIGMA_MEAN_DIST;
+    out->sigma = 0.f;
+    out->value_scale_by_set_size = 1;
+    out->enforce_budget = 1;
+    return KVM_OK;
+}
+
+int32_t kvm_out_capacity(const kvm_shape *shape, const kvm_params *params)
+{
+    if (check_shape(shape, "kvm_out_capacity") != KVM_OK || check_params(params, "kvm_out_capacity") != KVM_OK) return -1;
+    return capacity(shape, params);
+}
+
+size_t kvm_workspace_bytes(const kvm_shape *shape, const kvm_params *params)
+{
+    if (check_shape(shape, "kvm_workspace_bytes") != KVM_OK) return 0;
+    (void)params;
+    const size_t a = ws_attn(shape), b = ws_identify(shape);
+    return (a > b ? a : b) + 256;
+}
+
+kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, float *mass, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_attn_mass");
+    if (rc != KVM_OK) return rc;
+    const bool empty = (long long)shape->B * shape->N == 0;
+    if (!empty && (!Q || !K || !mass)) { set_error("kvm_attn_mass: Q, K and mass must not be NULL"); return KVM_ERR_INVALID_ARG; }
+    if (empty) return KVM_OK;
+    if (!ws || ws_bytes < ws_attn(shape)) {
+        set_error("kvm_attn_mass: workspace of %zu bytes needed, %zu given", ws_attn(shape), ws ? ws_bytes : (size_t)0);
+        return KVM_ERR_WORKSPACE;
+    }
+    return launch_attn_mass(*shape, Q, K, mass, (float *)ws, (hipStream_t)stream);
+}
+
+kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, const void *K, const float *mass,
+                             int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets, float *sim_opt,
+                             int32_t *slice_status, void *ws, size_t ws_bytes, void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_identify_sets");
+    if (rc != KVM_OK) return rc;
+    rc = check_params(params, "kvm_identify_sets");
+    if (rc != KVM_OK) return rc;
+    if (shape->B == 0) return KVM_OK;
+    if (!set_start || !n_sets || !slice_status || (capacity(shape, params) > 0 && !pivot) ||
+        (shape->N > 0 && (!K || !mass || !set_id))) {
+        set_error("kvm_identify_sets: a required pointer is NULL");
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (ws_identify(shape) > 0 && (!ws || ws_bytes < ws_identify(shape))) {
+        set_error("kvm_identify_sets: workspace of %zu bytes needed, %zu given", ws_identify(shape), ws ? ws_bytes : (size_t)0);
+        return KVM_ERR_WORKSPACE;
+    }
+    const size_t tok = (size_t)shape->B * shape->H_kv * shape->N;
+    float *sim = sim_opt ? sim_opt : (float *)ws;
+    uint8_t *flags = (uint8_t *)ws + align_up(tok * sizeof(float), 256);
+    return launch_identify(*shape, *params, capacity(shape, params), K, mass, set_id, set_start, pivot, n_sets, sim,
+                           flags, slice_status, (hipStream_t)stream);
+}
+
+kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                     const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out, void *V_out,
+                     float *w_opt, void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    kvm_status rc = check_shape(shape, "kvm_merge");
+    if (rc != KVM_OK) return rc;
+    rc = check_params(params, "kvm_merge");
+    if (rc != KVM_OK) return rc;
+    const int cap = capacity(shape, params);
+    if ((long long)shape->B * shape->N == 0 || cap == 0) return KVM_OK;
+    if (!K || !V || !set_start || !pivot || !n_sets || !K_out || !V_out) {
+        set_error("kvm_merge: a required pointer is NULL");
+        return KVM_ERR_INVALID_ARG;
+    }
+    return launch_merge(*shape, *params, cap, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, (hipStream_t)stream);
+}
+
+const char *kvm_last_error(void) { return g_err; }
+
+const char *kvm_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,149 @@
+// Internal helpers shared by the HIP kernels of libkvm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvm.h"
+
+namespace kvm {
+
+constexpr int HEAD_DIM = 128;          // the only head dimension v1 supports
+constexpr int WAVE = 64;
+
+typedef _Float16 half_t;
+typedef __bf16 bf16_t;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// ---- a lane's 8 consecutive elements of a 128-wide row (chunk c of 16) --------------
+
+template <typename T> struct Elem;
+
+template <> struct Elem<half_t> {
+    static constexpr int kDtype = KVM_F16;
+    struct Raw { u32x4 v; };
+    static __device__ __forceinline__ Raw load(const half_t *row, int c) {
+        return Raw{*reinterpret_cast<const u32x4 *>(row + c * 8)};
+    }
+    static __device__ __forceinline__ void store(half_t *row, int c, const Raw &r) {
+        *reinterpret_cast<u32x4 *>(row + c * 8) = r.v;
+    }
+    static __device__ __forceinline__ void to_float(const Raw &r, float *x) {
+        f16x8 h = __builtin_bit_cast(f16x8, r.v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = (float)h[i];
+    }
+    static __device__ __forceinline__ Raw from_float(const float *x) {
+        f16x8 h;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) h[i] = (half_t)x[i];   // round to nearest even
+        return Raw{__builtin_bit_cast(u32x4, h)};
+    }
+};
+
+template <> struct Elem<bf16_t> {
+    static constexpr int kDtype = KVM_BF16;
+    struct Raw { u32x4 v; };
+    static __device__ __forceinline__ Raw load(const bf16_t *row, int c) {
+        return Raw{*reinterpret_cast<const u32x4 *>(row + c * 8)};
+    }
+    static __device__ __forceinline__ void store(bf16_t *row, int c, const Raw &r) {
+        *reinterpret_cast<u32x4 *>(row + c * 8) = r.v;
+    }
+    static __device__ __forceinline__ void to_float(const Raw &r, float *x) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __builtin_bit_cast(float, r.v[i] << 16);
+            x[2 * i + 1] = __builtin_bit_cast(float, r.v[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ uint32_t rne(float f) {
+        uint32_t u = __builtin_bit_cast(uint32_t, f);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+        return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ Raw from_float(const float *x) {
+        Raw r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.v[i] = rne(x[2 * i]) | (rne(x[2 * i + 1]) << 16);
+        return r;
+    }
+};
+
+template <> struct Elem<float> {
+    static constexpr int kDtype = KVM_F32;
+    struct Raw { f32x4 a, b; };
+    static __device__ __forceinline__ Raw load(const float *row, int c) {
+        const f32x4 *p = reinterpret_cast<const f32x4 *>(row + c * 8);
+        return Raw{p[0], p[1]};
+    }
+    static __device__ __forceinline__ void store(float *row, int c, const Raw &r) {
+        f32x4 *p = reinterpret_cast<f32x4 *>(row + c * 8);
+        p[0] = r.a;
+        p[1] = r.b;
+    }
+    static __device__ __forceinline__ void to_float(const Raw &r, float *x) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[i] = r.a[i]; x[4 + i] = r.b[i]; }
+    }
+    static __device__ __forceinline__ Raw from_float(const float *x) {
+        Raw r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { r.a[i] = x[i]; r.b[i] = x[4 + i]; }
+        return r;
+    }
+};
+
+// ---- cross-lane helpers -------------------------------------------------------------
+
+// DPP move within a row of 16 lanes; every lane is enabled so no old value is needed.
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_f<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);   // row_half_mirror: quad q <-> quad 1-q within each half row
+    v += dpp_f<0x140>(v);   // row_mirror: lane i <-> lane 15-i
+    return v;
+}
+
+// Sum over the four 16-lane rows of a wave (same lane position in each row).
+__device__ __forceinline__ float rows4_sum(float v) {
+    v += __shfl_xor(v, 16, WAVE);
+    v += __shfl_xor(v, 32, WAVE);
+    return v;
+}
+
+// Order-preserving map of a finite float onto uint32 (-0 and +0 map to the same key).
+__device__ __forceinline__ uint32_t sortable_key(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int clamp_len(const int32_t *seq_lens, int b, int N) {
+    int n = seq_lens ? seq_lens[b] : N;
+    return n < 0 ? 0 : (n > N ? N : n);
+}
+
+// ---- host side -----------------------------------------------------------------------
+
+void set_error(const char *fmt, ...);
+kvm_status check_launch(const char *what);
+
+kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse,
+                            hipStream_t st);
+kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,
+                           const float *mass, int32_t *set_id, int32_t *set_start, int32_t *pivot,
+                           int32_t *n_sets, float *sim, uint8_t *flags, int32_t *slice_status, hipStream_t st);
+kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
+                        const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
+                        void *V_out, float *w_opt, hipStream_t st);
+
+}  // namespace kvm

@@ -1,0 +1,109 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before any launch (no GPU needed: these calls return
+before touching the device)."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from paper_2407_08454_amd import binding as kb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "kvm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(kvm_[a-z_]+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kb.load_library()
+    names = _declared()
+    assert names == set(kb.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert re.fullmatch(r"\d+\.\d+\.\d+", lib.kvm_version().decode())
+
+
+def test_presets_follow_the_printed_hyperparameters():
+    p = kb.kvm_params_for_budget(0.5)
+    assert (p.budget, p.recent_ratio, p.heavy_ratio, p.threshold) == (0.5, 0.17, 0.12, 0.75)
+    p = kb.kvm_params_for_budget(0.35)
+    assert (p.budget, p.recent_ratio, p.heavy_ratio, p.threshold) == (0.35, 0.08, 0.02, 0.75)
+    assert p.enforce_budget == 1 and p.value_scale_by_set_size == 1 and p.sigma_mode == kb.KVM_SIGMA_MEAN_DIST
+    p = kb.kvm_params_for_budget(0.25)
+    assert p.recent_ratio + p.heavy_ratio < 0.25
+    with pytest.raises(kb.KvmError):
+        kb.kvm_params_for_budget(0.0)
+    with pytest.raises(kb.KvmError):
+        kb.kvm_params_for_budget(1.5)
+
+
+def _shape(**kw):
+    d = dict(B=2, H_kv=3, G=1, N=100, d=128, dtype=kb.KVM_F16, seq_lens=None)
+    d.update(kw)
+    return kb.KvmShape(**d)
+
+
+def test_capacity_and_workspace():
+    p = kb.kvm_params_for_budget(0.35)
+    assert kb.kvm_out_capacity(_shape(N=4096), p) == 1433 == math.floor(0.35 * 4096)
+    p.enforce_budget = 0
+    assert kb.kvm_out_capacity(_shape(N=4096), p) == 4096
+    sh = _shape(B=4, H_kv=8, G=4, N=1000)
+    need = kb.kvm_workspace_bytes(sh, p)
+    assert need >= 4 * 8 * 4 * 1000 * 4 and need >= 4 * 8 * 1000 * 5
+    assert kb.kvm_workspace_bytes(_shape(d=64), p) == 0
+
+
+def test_host_detectable_errors_return_before_any_launch():
+    lib = kb.load_library()
+    p = kb.kvm_params_for_budget(0.5)
+    one = ctypes.c_void_p(256)            # never dereferenced: the calls fail before any launch
+
+    def attn(sh, Q=one, K=one, mass=one, ws=one, nbytes=1 << 30):
+        return lib.kvm_attn_mass(ctypes.byref(sh), Q, K, mass, ws, nbytes, None)
+
+    assert attn(_shape(d=64)) == kb.KVM_ERR_UNSUPPORTED and b"head dimension" in lib.kvm_last_error()
+    assert attn(_shape(dtype=7)) == kb.KVM_ERR_UNSUPPORTED
+    assert attn(_shape(G=0)) == kb.KVM_ERR_INVALID_ARG
+    assert attn(_shape(N=-1)) == kb.KVM_ERR_INVALID_ARG
+    assert attn(_shape(), Q=None) == kb.KVM_ERR_INVALID_ARG
+    assert attn(_shape(), ws=None) == kb.KVM_ERR_WORKSPACE
+    assert attn(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"workspace" in lib.kvm_last_error()
+    assert lib.kvm_attn_mass(None, one, one, one, one, 0, None) == kb.KVM_ERR_INVALID_ARG
+
+    def ident(sh, pr, ws=one, nbytes=1 << 30, K=one):
+        return lib.kvm_identify_sets(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, None, one, ws,
+                                     nbytes, None)
+
+    bad = kb.make_params(0.5, 0.4, 0.3)                  # conserved fraction above the budget
+    assert ident(_shape(), bad) == kb.KVM_ERR_INVALID_ARG and b"exceeds the budget" in lib.kvm_last_error()
+    assert ident(_shape(), kb.make_params(1.5, 0.1, 0.1)) == kb.KVM_ERR_INVALID_ARG
+    assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, threshold=float("nan"))) == kb.KVM_ERR_INVALID_ARG
+    assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, sigma_mode=5)) == kb.KVM_ERR_UNSUPPORTED
+    assert ident(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
+    assert ident(_shape(), p, nbytes=8) == kb.KVM_ERR_WORKSPACE
+
+    def merge(sh, pr, K=one):
+        return lib.kvm_merge(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, one, None, None, 0, None)
+
+    assert merge(_shape(), kb.make_params(0.5, 0.1, 0.1, sigma_mode=kb.KVM_SIGMA_FIXED, sigma=0.0)) == kb.KVM_ERR_INVALID_ARG
+    assert merge(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
+    assert merge(_shape(d=256), p) == kb.KVM_ERR_UNSUPPORTED
+
+
+def test_binding_refuses_mismatched_tensors_on_the_host():
+    import torch
+    K = torch.zeros((1, 2, 8, 128), dtype=torch.float16)
+    sh = kb.make_shape(K)
+    assert (sh.B, sh.H_kv, sh.N, sh.d, sh.dtype) == (1, 2, 8, 128, kb.KVM_F16)
+    with pytest.raises(ValueError):
+        kb.make_shape(K[:, :, ::2])                       # not contiguous
+    with pytest.raises(ValueError):
+        kb.make_shape(K.to(torch.float64))
+    with pytest.raises(ValueError):                       # CPU tensors never reach the library
+        kb.kvm_attn_mass(sh, K, K, torch.zeros((1, 2, 8)), torch.zeros(1024, dtype=torch.uint8))

@@ -1,0 +1,416 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the fp64
+oracle on the same seeded inputs.
+
+Bars: index maps bit-exact (similarities within 1e-6 of the threshold are counted and
+excused); attention mass within 2e-3 elementwise; merged K/V within 2e-3 plus the unit
+roundoff of the cache dtype they are stored in (row-normalised), and within one storage ulp
+of the exact value up to 2e-5 of the row maximum; singleton sets bit-identical.  Each stage is fed oracle-made
+inputs (mass rounded to fp32, index maps), never outputs of the HIP path.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2407_08454_amd import binding as kb
+from paper_2407_08454_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def _rand(shape, dtype, seed):
+    return synth.to_storage(np.random.default_rng(seed).standard_normal(shape, dtype=np.float32), dtype)
+
+
+def _slices(seed, B, H, n_list, N, d, G, dtype, rho=None):
+    """(B, H) independent slices from the workload generator, right-padded to N."""
+    Q = np.empty((B, H * G, N, d), synth.storage_numpy_dtype(dtype))
+    K = np.empty((B, H, N, d), Q.dtype)
+    V = np.empty_like(K)
+    for b in range(B):
+        for h in range(H):
+            q, k, v, _ = synth.gen_slice(seed, b * H + h, n_list[b], d, G, rho, dtype, N)
+            Q[b, h * G:(h + 1) * G], K[b, h], V[b, h] = q, k, v
+    return Q, K, V
+
+
+# ---------------------------------------------------------------------------------------------
+# (a) aggregated attention mass
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("n", [1, 2, 31, 63, 64, 65, 257, 600])
+def test_mass_small_sizes(dtype, n):
+    _say(f"mass dtype={dtype} n={n}")
+    Q, K, _ = _slices(11, 1, 3, [n], n, 128, 1, dtype)
+    want = ref.attn_mass(Q, K, dtype)
+    got = gu.gpu_mass(Q, K, dtype)
+    gu.assert_mass_close(got, want, None, n, f"{dtype} n={n}")
+    assert got.sum() == pytest.approx(3 * n, rel=1e-4)
+
+
+@pytest.mark.parametrize("dtype,G", [("bf16", 4), ("f16", 2), ("f32", 4)])
+def test_mass_grouped_queries_and_ragged(dtype, G):
+    lens = [300, 129, 0, 1, 256]
+    N = 320
+    _say(f"mass ragged dtype={dtype} G={G} lens={lens} N={N}")
+    Q, K, _ = _slices(12, len(lens), 2, lens, N, 128, G, dtype)
+    want = ref.attn_mass(Q, K, dtype, G=G, seq_lens=lens)
+    got = gu.gpu_mass(Q, K, dtype, G=G, seq_lens=lens)
+    gu.assert_mass_close(got, want, lens, N, f"{dtype} G={G} ragged")
+
+
+def test_mass_config1_and_determinism():
+    cfg = synth.CONFIGS[1]
+    _say("mass config 1 (N=512 fp32), two runs")
+    Q, K, V, _ = synth.gen_config(cfg)
+    want = ref.attn_mass(Q, K, "f32")
+    got = gu.gpu_mass(Q, K, "f32")
+    err = gu.assert_mass_close(got, want, None, 512, "config 1")
+    _say(f"  worst relative error {err:.2e}")
+    assert np.array_equal(got, gu.gpu_mass(Q, K, "f32"))          # no atomics: bitwise repeatable
+
+
+def test_mass_large_scores_do_not_overflow():
+    # keys and queries scaled so that raw scores reach the hundreds: the row maximum must be used
+    n = 200
+    Q, K, _ = _slices(13, 1, 2, [n], n, 128, 1, "f16")
+    Q = (Q.astype(np.float32) * 6).astype(np.float16)
+    K = (K.astype(np.float32) * 6).astype(np.float16)
+    want = ref.attn_mass(Q, K, "f16")
+    got = gu.gpu_mass(Q, K, "f16")
+    # columns that receive next to nothing are compared absolutely
+    assert np.isfinite(got).all() and got.sum() == pytest.approx(2 * n, rel=1e-4)
+    big = want > 1e-6
+    assert (np.abs(got - want)[big] / want[big]).max() <= gu.TOL
+
+
+# ---------------------------------------------------------------------------------------------
+# (b) merging sets
+# ---------------------------------------------------------------------------------------------
+
+def _identify_both(K, mass64, dtype, params, lens=None):
+    mass32 = mass64.astype(np.float32)
+    B, H, N, _ = K.shape
+    g = gu.gpu_identify(K, mass32, dtype, params, lens)
+    o = ref.identify_sets(K, mass32.astype(np.float64), dtype, params.budget, params.recent_ratio,
+                          params.heavy_ratio, params.threshold, bool(params.enforce_budget), g["cap_rows"], lens)
+    return g, o
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("n", [1, 2, 15, 16, 17, 255, 256, 257, 1000, 4096, 5000])
+def test_identify_sizes(dtype, n):
+    _say(f"identify dtype={dtype} n={n}")
+    Q, K, V = _slices(21, 2, 2, [n, n], n, 128, 1, dtype)
+    rng = np.random.default_rng(n)
+    mass = rng.random((2, 2, n)) ** 3 + 1e-3
+    params = kb.kvm_params_for_budget(0.5)
+    g, o = _identify_both(K, mass, dtype, params)
+    np.testing.assert_allclose(g["sim"], o["sim"], atol=2e-6)
+    exc, near = gu.compare_maps(g, o, None, n, params.threshold, f"{dtype} n={n}")
+    _say(f"  excused slices {exc}, near-threshold similarities {near}")
+    gu.check_partition(g, None, n, g["cap_rows"])
+
+
+@pytest.mark.parametrize("budget", [0.5, 0.35])
+def test_identify_with_oracle_mass_on_workload_slices(budget):
+    n = 1024
+    _say(f"identify on oracle mass, budget={budget}")
+    Q, K, V = _slices(22, 1, 6, [n], n, 128, 1, "f16")
+    mass = ref.attn_mass(Q, K, "f16")
+    params = kb.kvm_params_for_budget(budget)
+    g, o = _identify_both(K, mass, "f16", params)
+    exc, near = gu.compare_maps(g, o, None, n, params.threshold, f"budget {budget}")
+    assert (o["n_sets"] <= math.floor(budget * n)).all() and (g["status"] == 0).all()
+    _say(f"  sets per slice {g['n_sets'].ravel().tolist()}, excused {exc}, near {near}")
+
+
+def test_identify_ragged_and_padding_garbage():
+    lens = [700, 64, 0, 1, 333, 1023]
+    N = 1024
+    _say(f"identify ragged lens={lens}")
+    Q, K, V = _slices(23, len(lens), 2, lens, N, 128, 1, "bf16")
+    mass = np.random.default_rng(5).random((len(lens), 2, N)) + 0.01
+    params = kb.kvm_params_for_budget(0.35)
+    g, o = _identify_both(K, mass, "bf16", params, lens)
+    gu.compare_maps(g, o, lens, N, params.threshold, "ragged")
+    gu.check_partition(g, lens, N, g["cap_rows"])
+    for b, n in enumerate(lens):
+        assert (g["sim"][b, :, n:] == 0).all()
+
+
+def test_identify_special_keys():
+    n, d = 300, 128
+    _say("identify: identical keys, orthogonal keys, zero row")
+    params = kb.make_params(1.0, 0.1, 0.05, enforce_budget=False)
+    mass = np.linspace(2, 1, n)[None, None].repeat(3, 1)
+    K = np.zeros((1, 3, n, d), np.float32)
+    K[0, 0] = np.arange(1, d + 1)                      # identical keys
+    K[0, 1, np.arange(n), np.arange(n) % d] = 1.0      # neighbours orthogonal
+    K[0, 2] = np.random.default_rng(0).standard_normal((n, d))
+    K[0, 2, 100:110] = K[0, 2, 100]                    # a run of equal keys ...
+    K[0, 2, 105] = 0                                   # ... split by a zero-norm key
+    g, o = _identify_both(K, mass, "f32", params)
+    gu.compare_maps(g, o, None, n, params.threshold, "special keys")
+    assert g["n_sets"][0, 0] == 30 + 15 + 1 and g["n_sets"][0, 1] == n
+    assert g["sim"][0, 2, 105] == 0 and g["sim"][0, 2, 106] == 0
+
+
+def test_identify_ties_in_mass():
+    n = 2000
+    _say("identify: heavy ties in the scores (top-k and pivot tie-breaks)")
+    Q, K, V = _slices(24, 1, 4, [n], n, 128, 1, "f16", rho=0.97)
+    rng = np.random.default_rng(3)
+    mass = rng.integers(1, 6, size=(1, 4, n)).astype(np.float64)      # five distinct values only
+    mass[0, 3] = 1.0                                                    # all equal
+    for budget in (0.5, 0.35):
+        params = kb.kvm_params_for_budget(budget)
+        g, o = _identify_both(K, mass, "f16", params)
+        gu.compare_maps(g, o, None, n, params.threshold, f"ties budget {budget}")
+
+
+@pytest.mark.parametrize("case", ["fallback", "fallback_ties", "no_enforce"])
+def test_identify_budget_rule(case):
+    n = 1500
+    _say(f"identify budget rule: {case}")
+    rng = np.random.default_rng(7)
+    if case == "fallback_ties":
+        # keys cycle through three directions: every boundary similarity takes one of three values
+        base = rng.standard_normal((3, 128)).astype(np.float32)
+        K = base[np.arange(n) % 3][None, None].copy()
+    else:
+        K = rng.standard_normal((1, 1, n, 128)).astype(np.float32)     # neighbours nearly orthogonal
+    K = np.concatenate([K, _slices(25, 1, 1, [n], n, 128, 1, "f32", rho=0.8)[1]], axis=1)
+    mass = rng.random((1, 2, n)) + 0.1
+    params = kb.make_params(0.4, 0.1, 0.1, threshold=0.75, enforce_budget=(case != "no_enforce"))
+    g, o = _identify_both(K, mass, "f32", params)
+    exc, near = gu.compare_maps(g, o, None, n, params.threshold, case)
+    _say(f"  status {g['status'].ravel().tolist()} n_sets {g['n_sets'].ravel().tolist()} excused {exc}")
+    if case == "no_enforce":
+        assert g["status"][0, 0] == 0 and g["n_sets"][0, 0] == n and g["cap_rows"] == n
+    else:
+        assert g["status"][0, 0] == kb.KVM_SLICE_FALLBACK and g["n_sets"][0, 0] == math.floor(0.4 * n)
+
+
+def test_identify_infeasible_budget_is_reported():
+    n = 400
+    _say("identify: conserved tokens alone exceed the budget")
+    K = np.random.default_rng(1).standard_normal((1, 1, n, 128)).astype(np.float32)
+    mass = np.random.default_rng(2).random((1, 1, n)) + 0.1
+    params = kb.make_params(0.3, 0.15, 0.15, threshold=2.0)             # nothing can merge at threshold 2
+    g, o = _identify_both(K, mass, "f32", params)
+    gu.compare_maps(g, o, None, n, params.threshold, "infeasible")
+    want = kb.KVM_SLICE_FALLBACK | kb.KVM_SLICE_INFEASIBLE | kb.KVM_SLICE_TRUNCATED
+    assert g["status"][0, 0] == want and g["n_sets"][0, 0] > g["cap_rows"]
+
+
+# ---------------------------------------------------------------------------------------------
+# (c) Gaussian-kernel merge
+# ---------------------------------------------------------------------------------------------
+
+def _merge_both(K, V, dtype, params, o, lens=None):
+    ko, vo, w, Kt, Vt = gu.gpu_merge(K, V, dtype, params, o["set_start"], o["pivot"], o["n_sets"], lens)
+    rk, rv, rw = ref.merge(K, V, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
+                           bool(params.value_scale_by_set_size), lens)
+    return ko, vo, w, rk, rv, rw, Kt, Vt
+
+
+def _check_merge(K, V, dtype, o, ko, vo, w, rk, rv, rw, Kt, Vt, what):
+    B, H, N, d = K.shape
+    worst_k = worst_v = worst_w = 0.0
+    for b in range(B):
+        for h in range(H):
+            M = min(int(o["n_sets"][b, h]), o["cap_rows"])
+            if M == 0:
+                continue
+            ek = gu.row_rel_err(ko[b, h, :M], rk[b, h, :M])
+            ev = gu.row_rel_err(vo[b, h, :M], rv[b, h, :M])
+            worst_k, worst_v = max(worst_k, ek.max()), max(worst_v, ev.max())
+            # beyond the one rounding to the cache dtype only fp32 accumulation error remains
+            xk = gu.ulp_excess(ko[b, h, :M], rk[b, h, :M], dtype).max()
+            xv = gu.ulp_excess(vo[b, h, :M], rv[b, h, :M], dtype).max()
+            assert xk <= 2e-5 and xv <= 2e-5, f"{what}: error beyond one storage ulp {xk:.2e}/{xv:.2e}"
+            st = o["set_start"][b, h]
+            single = np.flatnonzero(np.diff(st[:M + 1]) == 1)
+            src = st[single]
+            k64, v64 = synth.to_f64(K[b, h], dtype), synth.to_f64(V[b, h], dtype)
+            assert np.array_equal(ko[b, h, single], k64[src]), f"{what}: singleton key rows are not bit-identical"
+            assert np.array_equal(vo[b, h, single], v64[src]), f"{what}: singleton value rows are not bit-identical"
+            if w is not None:
+                n_cov = st[M]
+                worst_w = max(worst_w, np.abs(w[b, h, :n_cov] - rw[b, h, :n_cov]).max())
+    tol = gu.kv_tol(dtype)
+    assert worst_k <= tol and worst_v <= tol, f"{what}: merged K/V error {worst_k:.3e}/{worst_v:.3e} > {tol:.3e}"
+    assert worst_w <= 1e-5, f"{what}: weight error {worst_w:.3e}"
+    return worst_k, worst_v, worst_w
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("budget", [0.5, 0.35])
+def test_merge_on_workload_slices(dtype, budget):
+    n = 1536
+    _say(f"merge dtype={dtype} budget={budget}")
+    Q, K, V = _slices(31, 2, 3, [n, n], n, 128, 1, dtype)
+    mass = np.random.default_rng(9).random((2, 3, n)) ** 3 + 1e-3
+    params = kb.kvm_params_for_budget(budget)
+    cap = math.floor(budget * n)
+    o = ref.identify_sets(K, mass, dtype, params.budget, params.recent_ratio, params.heavy_ratio, params.threshold,
+                          True, cap)
+    res = _merge_both(K, V, dtype, params, o)
+    errs = _check_merge(K, V, dtype, o, *res, f"{dtype} budget {budget}")
+    _say(f"  worst K/V/w errors {errs[0]:.2e} {errs[1]:.2e} {errs[2]:.2e}; "
+         f"largest set {int(np.diff(o['set_start'][0, 0, :o['n_sets'][0, 0] + 1]).max())}")
+
+
+@pytest.mark.parametrize("mode", ["fixed_sigma", "no_value_scale", "fixed_sigma_small"])
+def test_merge_variants(mode):
+    n = 800
+    _say(f"merge variant {mode}")
+    Q, K, V = _slices(32, 1, 4, [n], n, 128, 1, "f16")
+    mass = np.random.default_rng(4).random((1, 4, n)) + 0.01
+    kw = dict(fixed_sigma=dict(sigma_mode=kb.KVM_SIGMA_FIXED, sigma=5.0),
+              fixed_sigma_small=dict(sigma_mode=kb.KVM_SIGMA_FIXED, sigma=0.5),
+              no_value_scale=dict(value_scale_by_set_size=False))[mode]
+    params = kb.make_params(0.5, 0.17, 0.12, **kw)
+    o = ref.identify_sets(K, mass, "f16", 0.5, 0.17, 0.12, 0.75, True, n // 2)
+    res = _merge_both(K, V, "f16", params, o)
+    _check_merge(K, V, "f16", o, *res, mode)
+
+
+def test_merge_degenerate_sets():
+    n, d = 3000, 128
+    _say("merge: one set spanning the whole slice; identical keys; ragged; truncated capacity")
+    rng = np.random.default_rng(6)
+    lens = [n, 37, 0]
+    K = rng.standard_normal((3, 2, n, d)).astype(np.float32)
+    V = rng.standard_normal((3, 2, n, d)).astype(np.float32)
+    K[0, 1] = K[0, 1, 0]                                  # identical keys: uniform weights
+    mass = rng.random((3, 2, n)) + 0.1
+    params = kb.make_params(1.0, 0.0, 0.0, threshold=-2.0, enforce_budget=False)   # everything merges
+    o = ref.identify_sets(K, mass, "f32", 1.0, 0.0, 0.0, -2.0, False, n, lens)
+    assert o["n_sets"].ravel().tolist() == [1, 1, 1, 1, 0, 0]
+    res = _merge_both(K, V, "f32", params, o, lens)
+    _check_merge(K, V, "f32", o, *res, "degenerate")
+    # truncated: more sets than rows of capacity -> only the stored sets are merged
+    params = kb.make_params(0.3, 0.15, 0.15, threshold=2.0)
+    o = ref.identify_sets(K, mass, "f32", 0.3, 0.15, 0.15, 2.0, True, math.floor(0.3 * n), lens)
+    assert (o["status"][0] & kb.KVM_SLICE_TRUNCATED).all()
+    res = _merge_both(K, V, "f32", params, o, lens)
+    _check_merge(K, V, "f32", o, *res, "truncated")
+
+
+def test_merge_tolerates_inconsistent_maps():
+    n = 256
+    _say("merge: out-of-range map entries are clamped, nothing faults")
+    Q, K, V = _slices(33, 1, 1, [n], n, 128, 1, "f16")
+    params = kb.make_params(0.5, 0.1, 0.1)
+    cap = n // 2
+    st = np.full((1, 1, cap + 1), 10 ** 9, np.int32)
+    st[0, 0, :4] = [-5, 3, 2, 100000]
+    pv = np.full((1, 1, cap), -(10 ** 9), np.int32)
+    ko, vo, w, Kt, Vt = gu.gpu_merge(K, V, "f16", params, st, pv, np.array([[10 ** 6]], np.int32), want_w=False)
+    assert np.isfinite(ko).all() and np.isfinite(vo).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# whole pass
+# ---------------------------------------------------------------------------------------------
+
+def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
+    """GPU: the three calls back to back on all slices.  Oracle: the same on sampled slices.
+    Stage by stage the oracle's inputs are its own; the end-to-end maps are compared too and
+    slices whose maps differ (a near-tie in independently computed mass) are counted."""
+    Qd, Kd, Vd = gu.to_dev(Q, dtype), gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+    sl = gu.lens_dev(lens)
+    sh = kb.make_shape(Kd, G, sl)
+    buf = kb.Buffers(sh, params, "cuda", gu.TORCH_DT[dtype], with_debug=True)
+    kb.compress(sh, params, Qd, Kd, Vd, buf)
+    torch.cuda.synchronize()
+    B, H, N, d = K.shape
+    g = dict(set_id=buf.set_id.cpu().numpy(), set_start=buf.set_start.cpu().numpy(), pivot=buf.pivot.cpu().numpy(),
+             n_sets=buf.n_sets.cpu().numpy(), status=buf.status.cpu().numpy(), sim=buf.sim.cpu().numpy())
+    gu.check_partition(g, lens, N, buf.cap, what)
+    mass_g = buf.mass.cpu().numpy()
+    differing = 0
+    for (b, h) in sample:
+        n = N if lens is None else int(lens[b])
+        _say(f"  {what}: oracle on slice ({b},{h}) n={n}")
+        Qs = np.ascontiguousarray(Q[b:b + 1, h * G:(h + 1) * G])
+        Ks, Vs = np.ascontiguousarray(K[b:b + 1, h:h + 1]), np.ascontiguousarray(V[b:b + 1, h:h + 1])
+        ls = None if lens is None else [n]
+        if G > 1:      # the query heads in parallel: the grouped score is the sum of the heads' scores
+            m_o = ref.attn_mass(Qs.transpose(1, 0, 2, 3).copy(), np.repeat(Ks, G, 0), dtype,
+                                seq_lens=None if ls is None else ls * G).sum(0, keepdims=True)
+        else:
+            m_o = ref.attn_mass(Qs, Ks, dtype, seq_lens=ls)
+        gu.assert_mass_close(mass_g[b:b + 1, h:h + 1], m_o, ls, N, f"{what} ({b},{h})")
+        # stage (b) and (c) on the oracle's own fp32-rounded mass
+        m32 = m_o.astype(np.float32)
+        gi = gu.gpu_identify(Ks, m32, dtype, params, ls)
+        oi = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
+                               params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"], ls)
+        gu.compare_maps(gi, oi, ls, N, params.threshold, f"{what} ({b},{h})")
+        res = _merge_both(Ks, Vs, dtype, params, oi, ls)
+        _check_merge(Ks, Vs, dtype, oi, *res, f"{what} ({b},{h})")
+        # end to end: GPU maps from GPU mass against oracle maps from oracle mass
+        same = all(np.array_equal(g[k][b, h], oi[k][0, 0]) for k in ("set_id", "set_start", "pivot"))
+        if same:
+            M = min(int(oi["n_sets"][0, 0]), buf.cap)
+            ek = gu.row_rel_err(gu.to_host_f64(buf.K_out[b, h, :M]), res[3][0, 0, :M]).max() if M else 0.0
+            ev = gu.row_rel_err(gu.to_host_f64(buf.V_out[b, h, :M]), res[4][0, 0, :M]).max() if M else 0.0
+            assert ek <= gu.kv_tol(dtype) and ev <= gu.kv_tol(dtype), \
+                f"{what} ({b},{h}): end-to-end K/V error {ek:.2e}/{ev:.2e}"
+        else:
+            differing += 1
+    _say(f"  {what}: {differing} of {len(sample)} sampled slices have end-to-end maps that differ (mass near-ties)")
+    assert differing <= max(1, len(sample) // 4)
+    return g
+
+
+def test_whole_pass_config1():
+    cfg = synth.CONFIGS[1]
+    _say("whole pass: config 1")
+    Q, K, V, _ = synth.gen_config(cfg)
+    g = _whole_pass(Q, K, V, "f32", 1, kb.kvm_params_for_budget(0.5), None, [(0, 0)], "config 1")
+    assert g["n_sets"][0, 0] <= 256 and g["status"][0, 0] == 0
+
+
+@pytest.mark.parametrize("cfg_id,layers,budget", [(2, 2, 0.5), (2, 1, 0.35), (3, 1, 0.35)])
+def test_whole_pass_reduced_layers(cfg_id, layers, budget):
+    cfg = synth.CONFIGS[cfg_id]
+    _say(f"whole pass: config {cfg_id}, {layers} layer(s), budget {budget}")
+    Q, K, V, lens = synth.gen_config(cfg, layers=layers)
+    H = cfg["H_kv"]
+    sample = [(0, 0), (layers - 1, H - 1), (0, H // 2)]
+    g = _whole_pass(Q, K, V, cfg["dtype"], cfg["G"], kb.kvm_params_for_budget(budget), lens, sample,
+                    f"config {cfg_id}")
+    assert (g["n_sets"] <= math.floor(budget * cfg["N"])).all()
+    _say(f"  mean M/n = {g['n_sets'].mean() / cfg['N']:.3f}, fallback slices {(g['status'] != 0).sum()}")
+
+
+def test_whole_pass_config4_grouped_queries_long():
+    cfg = synth.CONFIGS[4]
+    _say("whole pass: config 4 shape (G=4, N=16384), one layer")
+    Q, K, V, lens = synth.gen_config(cfg, layers=1)
+    g = _whole_pass(Q, K, V, "bf16", 4, kb.kvm_params_for_budget(0.5), None, [(0, 3)], "config 4")
+    assert (g["n_sets"] <= 8192).all()
+
+
+def test_whole_pass_config5_ragged_batch():
+    cfg = dict(synth.CONFIGS[5], H_kv=4)         # four of the 32 heads of one layer, all four lengths
+    _say("whole pass: config 5 shape (B=4 ragged, N=16384 padded), one layer, 4 heads")
+    Q, K, V, lens = synth.gen_config(cfg, layers=1)
+    g = _whole_pass(Q, K, V, "f16", 1, kb.kvm_params_for_budget(0.35), lens, [(0, 0), (1, 1), (2, 2), (3, 3)],
+                    "config 5")
+    for b, n in enumerate(lens):
+        assert (g["n_sets"][b] <= math.floor(0.35 * n)).all()
