@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole KV-merging compression pass on one MI355X.
+
+A step = one pass of the hot path (kvm_attn_mass, kvm_identify_sets, kvm_merge) over every
+(layer, KV-head) slice of the workload, inputs resident in HBM.  The default workload is the
+Llama2-7B shape (32 layers x 32 KV heads, N = 4096, d = 128, fp16, budget 0.5) on seeded
+synthetic Q/K/V.  Prints one JSON line; `roofline` describes the dominant kernel from HIP
+events recorded by the library on its launch stream inside the timed region, `cpu_baseline`
+is the fp64 oracle timed on the host cores on a sample of the same slices.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA = {"f16": 2.5e15, "bf16": 2.5e15, "f32": 157.3e12}   # dense matrix peaks, FLOP/s
+PEAK_HBM = 8.0e12                                               # B/s
+METRIC = "KV tokens compressed/sec (all layers x heads) at Llama2-7B N=4096"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="workload id (2 = the headline Llama2-7B shape)")
+    ap.add_argument("--layers", type=int, default=None, help="generate only this many layers (not the headline run)")
+    ap.add_argument("--budget", type=float, default=0.5)
+    ap.add_argument("--cpu-slices", type=int, default=64, help="slices the oracle is timed on (0 = skip)")
+    ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (slices are independent; see DESIGN.md for how it "
+              "would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2407_08454_amd import binding as kb
+    from paper_2407_08454_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    dtype = cfg["dtype"]
+    t0 = time.time()
+    Q, K, V, lens = synth.gen_config(cfg, layers=args.layers)
+    gen_s = time.time() - t0
+    B, H, G, N, d = K.shape[0], cfg["H_kv"], cfg["G"], cfg["N"], cfg["d"]
+    n_per_b = np.full(B, N, np.int64) if lens is None else lens.astype(np.int64)
+    token_slices = int(n_per_b.sum()) * H
+
+    torch.cuda.set_device(0)
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+
+    def dev(x):
+        if dtype == "bf16":
+            return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(x).cuda()
+
+    Qd, Kd, Vd = dev(Q), dev(K), dev(V)
+    sl = None if lens is None else torch.from_numpy(lens).cuda()
+    params = kb.kvm_params_for_budget(args.budget)
+    shape = kb.make_shape(Kd, G, sl)
+    buf = kb.Buffers(shape, params, "cuda", tdt)
+
+    for _ in range(args.warmup):
+        kb.compress(shape, params, Qd, Kd, Vd, buf)
+    torch.cuda.synchronize()
+
+    if not args.no_profile:
+        kb.kvm_profile_enable(8 * args.steps)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e in ev:
+        e[0].record()
+        kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+        e[1].record()
+        kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, None,
+                             buf.status, buf.ws)
+        e[2].record()
+        kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None, buf.ws)
+        e[3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    stage_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in ev) for i in range(3)]
+    kernels = {}
+    if not args.no_profile:
+        kernels = {k: v[1] / max(v[0], 1) for k, v in kb.kvm_profile_collect().items()}
+        kb.kvm_profile_disable()
+
+    n_sets = buf.n_sets.cpu().numpy().astype(np.int64)
+    status = buf.status.cpu().numpy()
+    M_total = int(n_sets.sum())
+
+    # ---- roofline of the dominant kernel -----------------------------------------------------
+    esz = 4 if dtype == "f32" else 2
+    # algorithmic work per launch: one causal QK^T for each attention kernel; bytes streamed once
+    flops_attn = float(sum(G * n * (n + 1) * d for n in n_per_b) * H)
+    bytes_cos = float(token_slices * d * esz + token_slices * 4)
+    bytes_merge = float(2 * token_slices * d * esz + 2 * M_total * d * esz + 8 * M_total)
+    roofline = None
+    hbm = {}
+    if kernels:
+        dom = max(kernels, key=kernels.get)
+        if dom.startswith("attn"):
+            ach = flops_attn / (kernels[dom] * 1e-3)
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": ach / 1e12, "peak": PEAK_MFMA[dtype] / 1e12,
+                        "unit": "TFLOP/s", "frac": ach / PEAK_MFMA[dtype], "traffic": None,
+                        "ms_per_launch": kernels[dom]}
+        else:
+            byts = bytes_merge if dom == "merge_kernel" else bytes_cos
+            ach = byts / (kernels[dom] * 1e-3)
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                        "frac": ach / PEAK_HBM, "traffic": None, "ms_per_launch": kernels[dom]}
+        for name, byts in (("cosine_scan_kernel", bytes_cos), ("merge_kernel", bytes_merge)):
+            if name in kernels:
+                hbm[name] = {"algorithmic_GB": byts / 1e9, "ms": kernels[name],
+                             "GB/s": byts / (kernels[name] * 1e-3) / 1e9,
+                             "frac_of_hbm_peak": byts / (kernels[name] * 1e-3) / PEAK_HBM}
+
+    # ---- the oracle on the host cores, on a sample of the same slices --------------------------
+    cpu = None
+    if args.cpu_slices > 0:
+        from oracle import ref
+        S = min(args.cpu_slices, B * H)
+        idx = np.linspace(0, B * H - 1, S).astype(int)          # spread over layers and heads
+        Ks = np.ascontiguousarray(K.reshape(B * H, N, d)[idx])[:, None]
+        Vs = np.ascontiguousarray(V.reshape(B * H, N, d)[idx])[:, None]
+        Qs = np.ascontiguousarray(Q.reshape(B * H, G, N, d)[idx])
+        ls = None if lens is None else lens[idx // H]
+        t0 = time.perf_counter()
+        m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
+        o = ref.identify_sets(Ks, m.astype(np.float32).astype(np.float64), dtype, params.budget, params.recent_ratio,
+                              params.heavy_ratio, params.threshold, True, buf.cap, ls)
+        ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], seq_lens=ls)
+        cpu_s = time.perf_counter() - t0
+        toks = int(N * S if ls is None else ls.sum())
+        cores = ref.num_threads()
+        cpu = {"value": toks / cpu_s, "unit": "token-slices/s", "cores": cores, "kind": "oracle",
+               "sample": f"{S} of {B * H} slices (evenly spaced over layers and heads), whole pass in fp64, "
+                         f"{cpu_s:.1f} s wall on {cores} OpenMP threads"}
+
+    out = {
+        "metric": METRIC, "value": token_slices / (ms_per_step * 1e-3), "unit": "token-slices/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] {cfg['name']}: {B // cfg['batch']} layers x {H} KV heads, "
+                               f"G={G}, N={N}, d={d}, {dtype}, budget {args.budget}, AR(1) keys seed {cfg['seed']}",
+                   "slices": B * H, "token_slices_per_step": token_slices, "merged_rows_per_step": M_total,
+                   "mean_M_over_n": M_total / token_slices, "slices_with_fallback": int((status != 0).sum())},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "stage_ms": {"attn_mass": stage_ms[0] / args.steps, "identify_sets": stage_ms[1] / args.steps,
+                     "merge": stage_ms[2] / args.steps},
+        "kernel_ms": kernels, "hbm_kernels": hbm, "input_generation_s": gen_s,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -177,6 +177,30 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
                      const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,
                      void *K_out, void *V_out, float *w_opt, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the method; no citation).  While
+ * enabled, every kernel the three calls launch is bracketed by two HIP events
+ * recorded on the launch stream, so the time is that of the kernel alone on the
+ * stream it runs on.  This is the library's only state and the only place where
+ * it creates anything (host-side event objects, in kvm_profile_enable):
+ *   kvm_profile_enable(max_launches)  creates 2*max_launches events; launches
+ *       beyond that are not timed.  Call with no library work in flight.
+ *   kvm_profile_collect(out, max)     waits for the recorded events, writes one
+ *       record per kernel name (at most max), returns the number of records,
+ *       and clears the recording so that it can be filled again.
+ *   kvm_profile_disable()             destroys the events.
+ * Not thread-safe: enable, launch and collect from one thread.
+ */
+typedef struct {
+    char name[48];            /* kernel name, e.g. "attn_colsum_kernel"          */
+    int32_t launches;         /* timed launches since the last collect          */
+    float total_ms;           /* sum of their durations in milliseconds         */
+} kvm_kernel_time;
+
+kvm_status kvm_profile_enable(int32_t max_launches);
+int32_t kvm_profile_collect(kvm_kernel_time *out, int32_t max_records);
+kvm_status kvm_profile_disable(void);
+
 /* Message of the calling thread's last failed call ("" if none).  Static storage. */
 const char *kvm_last_error(void);
 

@@ -45,6 +45,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 enum { REF_F32 = 0, REF_F16 = 1, REF_BF16 = 2 };
 enum { REF_SLICE_OK = 0, REF_SLICE_FALLBACK = 1, REF_SLICE_INFEASIBLE = 2, REF_SLICE_TRUNCATED = 4 };
@@ -393,6 +396,16 @@ int kvm_ref_merge(int B, int H, int N, int d, int dtype, const int32_t *seq_lens
         free(kd); free(vd); free(w);
     }
     return 0;
+}
+
+/* Threads the slice loops run on (for the benchmark's report). */
+int kvm_ref_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }
 
 /* Widening helpers exported for the tests (exactness of the fp16 / bf16 readers). */

@@ -70,6 +70,10 @@ def bf16_to_double(bits: int) -> float:
     return _load().kvm_ref_bf16_to_double(bits)
 
 
+def num_threads() -> int:
+    return int(_load().kvm_ref_num_threads())
+
+
 def attn_mass(Q, K, dtype: str, G: int = 1, seq_lens=None):
     """Q (B, H*G, N, d), K (B, H, N, d) -> mass (B, H, N) fp64."""
     lib = _load()

@@ -21,7 +21,8 @@ KVM_SLICE_FALLBACK, KVM_SLICE_INFEASIBLE, KVM_SLICE_TRUNCATED = 1, 2, 4
 KVM_SIGMA_MEAN_DIST, KVM_SIGMA_FIXED = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
-           "kvm_identify_sets", "kvm_merge", "kvm_last_error", "kvm_version")
+           "kvm_identify_sets", "kvm_merge", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
+           "kvm_last_error", "kvm_version")
 
 _TORCH_DTYPE = {torch.float32: KVM_F32, torch.float16: KVM_F16, torch.bfloat16: KVM_BF16}
 
@@ -35,6 +36,10 @@ class KvmParams(ctypes.Structure):
     _fields_ = [("budget", ctypes.c_double), ("recent_ratio", ctypes.c_double), ("heavy_ratio", ctypes.c_double),
                 ("threshold", ctypes.c_float), ("sigma_mode", ctypes.c_int32), ("sigma", ctypes.c_float),
                 ("value_scale_by_set_size", ctypes.c_int32), ("enforce_budget", ctypes.c_int32)]
+
+
+class KvmKernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int32), ("total_ms", ctypes.c_float)]
 
 
 class KvmError(RuntimeError):
@@ -67,6 +72,12 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_merge.restype = ctypes.c_int
+    lib.kvm_profile_enable.argtypes = [ctypes.c_int32]
+    lib.kvm_profile_enable.restype = ctypes.c_int
+    lib.kvm_profile_collect.argtypes = [ctypes.POINTER(KvmKernelTime), ctypes.c_int32]
+    lib.kvm_profile_collect.restype = ctypes.c_int32
+    lib.kvm_profile_disable.argtypes = []
+    lib.kvm_profile_disable.restype = ctypes.c_int
     lib.kvm_last_error.restype = ctypes.c_char_p
     lib.kvm_version.restype = ctypes.c_char_p
     _lib = lib
@@ -196,6 +207,21 @@ def kvm_merge(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets
         ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(set_start), _ptr(pivot), _ptr(n_sets),
         _ptr(K_out), _ptr(V_out), _ptr(w_opt), None if ws is None else _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_profile_enable(max_launches: int):
+    _check("kvm_profile_enable", load_library().kvm_profile_enable(int(max_launches)))
+
+
+def kvm_profile_collect() -> dict:
+    """{kernel name: (launches, total milliseconds)} since the last collect."""
+    recs = (KvmKernelTime * 16)()
+    n = load_library().kvm_profile_collect(recs, 16)
+    return {recs[i].name.decode(): (recs[i].launches, recs[i].total_ms) for i in range(n)}
+
+
+def kvm_profile_disable():
+    _check("kvm_profile_disable", load_library().kvm_profile_disable())
 
 
 class Buffers:

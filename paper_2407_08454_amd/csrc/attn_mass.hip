@@ -348,6 +348,7 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
     const int n_q = sh.B * sh.H_kv * sh.G, n_kv = sh.B * sh.H_kv;
     {
         const long long blocks = (long long)((n_q + 7) / 8) * 8 * tiles;
+        ProfScope prof("attn_lse_kernel", st);
         hipLaunchKernelGGL(attn_lse_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q, (const T *)K,
                            lse, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, tiles, c);
         kvm_status rc = check_launch("attn_lse_kernel");
@@ -355,6 +356,7 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
     }
     {
         const long long blocks = (long long)((n_kv + 7) / 8) * 8 * tiles;
+        ProfScope prof("attn_colsum_kernel", st);
         hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
                            (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, tiles, c);
         return check_launch("attn_colsum_kernel");

@@ -415,6 +415,7 @@ static void launch_cosine(const kvm_shape &sh, const void *K, float *sim, hipStr
 {
     const int tiles = (sh.N + COS_ROWS_PER_BLOCK - 1) / COS_ROWS_PER_BLOCK;
     const long long blocks = (long long)sh.B * sh.H_kv * tiles;
+    ProfScope prof("cosine_scan_kernel", st);
     hipLaunchKernelGGL(cosine_scan_kernel<T>, dim3((unsigned)blocks), dim3(COS_BLOCK), 0, st, (const T *)K, sim,
                        sh.seq_lens, sh.H_kv, sh.N, tiles);
 }
@@ -452,6 +453,7 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
     a.recent_ratio = pr.recent_ratio;
     a.heavy_ratio = pr.heavy_ratio;
     a.threshold = pr.threshold;
+    ProfScope prof("segment_kernel", st);
     hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), 0, st, a);
     return check_launch("segment_kernel");
 }

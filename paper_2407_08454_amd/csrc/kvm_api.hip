@@ -31,6 +31,28 @@ kvm_status check_launch(const char *what)
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---- optional per-kernel timing ---------------------------------------------------------
+struct ProfState {
+    bool on = false;
+    int cap = 0, used = 0;
+    hipEvent_t *ev = nullptr;        // 2 per timed launch
+    const char **names = nullptr;    // kernel name per timed launch (string literals)
+};
+static ProfState g_prof;
+
+ProfScope::ProfScope(const char *name, hipStream_t s) : slot(-1), st(s)
+{
+    if (!g_prof.on || g_prof.used >= g_prof.cap) return;
+    slot = g_prof.used++;
+    g_prof.names[slot] = name;
+    (void)hipEventRecord(g_prof.ev[2 * slot], st);
+}
+
+ProfScope::~ProfScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_prof.ev[2 * slot + 1], st);
+}
+
 static kvm_status check_shape(const kvm_shape *sh, const char *fn)
 {
     if (!sh) { set_error("%s: shape is NULL", fn); return KVM_ERR_INVALID_ARG; }
@@ -126,8 +148,8 @@ size_t kvm_workspace_bytes(const kvm_shape *shape, const kvm_params *params)
 {
     if (check_shape(shape, "kvm_workspace_bytes") != KVM_OK) return 0;
     (void)params;
-    const size_t a = ws_attn(shape), b = ws_identify(shape);
-    return (a > b ? a : b) + 256;
+    const size_t a = ws_attn(shape), b = ws_identify(shape), c = merge_workspace_bytes(*shape);
+    return (a > b ? (a > c ? a : c) : (b > c ? b : c)) + 256;
 }
 
 kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, float *mass, void *ws, size_t ws_bytes,
@@ -174,8 +196,6 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
                      const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out, void *V_out,
                      float *w_opt, void *ws, size_t ws_bytes, void *stream)
 {
-    (void)ws;
-    (void)ws_bytes;
     kvm_status rc = check_shape(shape, "kvm_merge");
     if (rc != KVM_OK) return rc;
     rc = check_params(params, "kvm_merge");
@@ -186,7 +206,69 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
         set_error("kvm_merge: a required pointer is NULL");
         return KVM_ERR_INVALID_ARG;
     }
-    return launch_merge(*shape, *params, cap, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, (hipStream_t)stream);
+    if (!ws || ws_bytes < merge_workspace_bytes(*shape)) {
+        set_error("kvm_merge: workspace of %zu bytes needed, %zu given", merge_workspace_bytes(*shape), ws ? ws_bytes : (size_t)0);
+        return KVM_ERR_WORKSPACE;
+    }
+    return launch_merge(*shape, *params, cap, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, (int32_t *)ws,
+                        (hipStream_t)stream);
+}
+
+kvm_status kvm_profile_disable(void)
+{
+    if (g_prof.ev) {
+        for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+        delete[] g_prof.ev;
+        delete[] g_prof.names;
+    }
+    g_prof = ProfState();
+    return KVM_OK;
+}
+
+kvm_status kvm_profile_enable(int32_t max_launches)
+{
+    kvm_profile_disable();
+    if (max_launches < 1 || max_launches > (1 << 20)) {
+        set_error("kvm_profile_enable: max_launches must lie in [1, 2^20]");
+        return KVM_ERR_INVALID_ARG;
+    }
+    g_prof.ev = new hipEvent_t[2 * (size_t)max_launches];
+    g_prof.names = new const char *[max_launches];
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+            g_prof.cap = i / 2;
+            kvm_profile_disable();
+            set_error("kvm_profile_enable: hipEventCreate failed");
+            return KVM_ERR_LAUNCH;
+        }
+    }
+    g_prof.cap = max_launches;
+    g_prof.used = 0;
+    g_prof.on = true;
+    return KVM_OK;
+}
+
+int32_t kvm_profile_collect(kvm_kernel_time *out, int32_t max_records)
+{
+    if (!g_prof.on || !out || max_records < 1) return 0;
+    int n = 0;
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess) continue;
+        if (hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess) continue;
+        int r = 0;
+        while (r < n && strcmp(out[r].name, g_prof.names[i]) != 0) ++r;
+        if (r == n) {
+            if (n == max_records) continue;
+            memset(&out[n], 0, sizeof(out[n]));
+            strncpy(out[n].name, g_prof.names[i], sizeof(out[n].name) - 1);
+            ++n;
+        }
+        out[r].launches += 1;
+        out[r].total_ms += ms;
+    }
+    g_prof.used = 0;
+    return n;
 }
 
 const char *kvm_last_error(void) { return g_err; }

@@ -137,6 +137,14 @@ __device__ __forceinline__ int clamp_len(const int32_t *seq_lens, int b, int N) 
 void set_error(const char *fmt, ...);
 kvm_status check_launch(const char *what);
 
+// Brackets one kernel launch with two events when profiling is enabled (see kvm_profile_*).
+struct ProfScope {
+    int slot;
+    hipStream_t st;
+    ProfScope(const char *name, hipStream_t st);
+    ~ProfScope();
+};
+
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse,
                             hipStream_t st);
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,
@@ -144,6 +152,7 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
                            int32_t *n_sets, float *sim, uint8_t *flags, int32_t *slice_status, hipStream_t st);
 kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
-                        void *V_out, float *w_opt, hipStream_t st);
+                        void *V_out, float *w_opt, int32_t *plan, hipStream_t st);
+size_t merge_workspace_bytes(const kvm_shape &sh);
 
 }  // namespace kvm

@@ -1,46 +1,92 @@
 // Gaussian-kernel weighted merging with a compacting write (Section 4.2: Def. 4.2 Eq. (4),
 // Eq. (5), (6); Algorithm 2).
 //
-// One wave owns MERGE_SETS_PER_WAVE consecutive output rows (sets) of one slice.  A row of
-// 128 elements is spread over 16 lanes (8 elements = 16 B each for 16-bit types), so one
-// wave instruction moves four rows.  Per set: one sweep over its keys for the distances to
-// the pivot (sigma), a second sweep (served by L1/L2, the set was just read) that forms the
-// weights and accumulates keys and values in fp32, then one rounded row is written per
-// output.  Runs of singleton sets are copied bit for bit, four rows per instruction.
-// HBM traffic: K once, V once, 2 M rows out.
+// Work is dealt out by tokens, not by sets, because set lengths are very uneven (most sets
+// are conserved singletons, most tokens sit in sets of 17..128): a small planning kernel
+// finds, for every tile of MERGE_TILE tokens, the first set that starts in it; one wave then
+// owns the sets that start inside its tile.  A row of 128 elements is spread over 16 lanes
+// (8 elements = 16 B each for 16-bit types), so one wave instruction moves four rows.  Per
+// set: one sweep over its keys for the distances to the pivot (sigma), a second sweep (served
+// by L2, the set was just read) that forms the weights and accumulates keys and values in
+// fp32, then one rounded row is written per output.  Loads are issued 32 rows at a time; a
+// set of up to 32 tokens is read exactly once and held in registers.  Runs of singleton sets
+// are copied bit for bit.  HBM traffic: K once, V once, 2 M rows out.
 #include "kvm_common.h"
 
 namespace kvm {
 
-constexpr int MERGE_BLOCK = 256;
-constexpr int MERGE_SETS_PER_WAVE = 16;
-constexpr int MERGE_SETS_PER_BLOCK = (MERGE_BLOCK / WAVE) * MERGE_SETS_PER_WAVE;
+constexpr int MERGE_BLOCK = 64;          // one wave per workgroup: waves finish independently
+constexpr int MERGE_TILE = 64;           // tokens per wave (its sets are those that start in the tile)
+constexpr int PLAN_BLOCK = 256;
+// 4-row groups whose loads are issued together: 32 rows (8 KB of K and 8 KB of V) for the
+// 16-bit types, 16 rows for fp32 (same bytes)
+template <typename T> struct MergeUnroll { static constexpr int value = sizeof(T) == 2 ? 8 : 4; };
 
 struct MergeArgs {
     const int32_t *set_start, *pivot, *n_sets, *seq_lens;
     float *w_opt;
-    int H, N, cap_rows, blocks_per_slice;
+    const int32_t *plan;    // (slices, tiles_per_slice + 1): first set starting at or after each tile
+    int H, N, cap_rows, tiles_per_slice;
     int sigma_fixed;        // 1: use inv_two_sigma_sq
     float inv_two_sigma_sq; // 1 / (2 sigma^2) for the fixed-sigma mode
     int value_scale;
 };
 
-template <typename T>
+// plan[t] = smallest s with set_start[s] >= t * MERGE_TILE (M if there is none), t = 0..tiles.
+__global__ __launch_bounds__(PLAN_BLOCK) void merge_plan_kernel(const int32_t *__restrict__ set_start,
+                                                                const int32_t *__restrict__ n_sets,
+                                                                const int32_t *__restrict__ seq_lens, int32_t *__restrict__ plan,
+                                                                int H, int N, int cap_rows, int tiles)
+{
+    const int slice = blockIdx.x;
+    const int n = clamp_len(seq_lens, slice / H, N);
+    const int M = min(max(n_sets[slice], 0), cap_rows);
+    const int32_t *sst = set_start + (size_t)slice * (cap_rows + 1);
+    int32_t *pl = plan + (size_t)slice * (tiles + 1);
+    for (int s = threadIdx.x; s <= M; s += PLAN_BLOCK) {
+        const int prev = s > 0 ? min(max(sst[s - 1], 0), n) : -1;
+        const int t_lo = prev < 0 ? 0 : prev / MERGE_TILE + 1;
+        const int t_hi = s < M ? min(min(max(sst[s], 0), n) / MERGE_TILE, tiles) : tiles;
+        for (int t = t_lo; t <= t_hi; ++t) pl[t] = s;
+    }
+}
+
+// Squared distance of 8 elements, summed over the 16 lanes of the row.
+__device__ __forceinline__ float sq_dist16(const float *kp, const float *x) {
+    float d[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d[e] = kp[e] - x[e];
+    const float s0 = fmaf(d[1], d[1], d[0] * d[0]), s1 = fmaf(d[3], d[3], d[2] * d[2]);
+    const float s2 = fmaf(d[5], d[5], d[4] * d[4]), s3 = fmaf(d[7], d[7], d[6] * d[6]);
+    return row16_sum((s0 + s1) + (s2 + s3));
+}
+
+// WITH_W: also write the per-token weights; FIXED: sigma given instead of derived from the
+// set.  Both are compile-time so that the row loops stay free of branches and the compiler
+// can interleave the independent rows.
+template <typename T, bool WITH_W, bool FIXED>
 __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict__ K, const T *__restrict__ V,
                                                             T *__restrict__ K_out, T *__restrict__ V_out, MergeArgs a)
 {
-    const int slice = blockIdx.x / a.blocks_per_slice;
-    const int blk = blockIdx.x - slice * a.blocks_per_slice;
+    using E = Elem<T>;
+    using Raw = typename E::Raw;
+    constexpr int U = MergeUnroll<T>::value;   // row groups (of 4 rows) in flight
+    constexpr int US = 4;                      // same for runs of singleton sets (16 = all of a wave's sets)
+    const int slice = blockIdx.x / a.tiles_per_slice;
+    const int tile = blockIdx.x - slice * a.tiles_per_slice;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
     const int slot = lane >> 4;          // which of the four rows of an instruction
     const int c = lane & 15;             // which 8-element chunk of the row
     const int n = clamp_len(a.seq_lens, slice / a.H, a.N);
-    int M = a.n_sets[slice];
-    if (M > a.cap_rows) M = a.cap_rows;
-    const int s_lo = blk * MERGE_SETS_PER_BLOCK + wave * MERGE_SETS_PER_WAVE;
-    if (s_lo >= M) return;
-    const int cnt = min(MERGE_SETS_PER_WAVE, M - s_lo);
+    if (tile * MERGE_TILE >= n) return;
+    const int M = min(max(a.n_sets[slice], 0), a.cap_rows);
+    // sets [s_lo, s_hi) start inside this tile (entries are clamped: the plan may hold garbage
+    // when the maps are inconsistent)
+    const int32_t *pl = a.plan + (size_t)slice * (a.tiles_per_slice + 1) + tile;
+    const int s_lo = min(max(pl[0], 0), M);
+    const int s_hi = min(max(pl[1], s_lo), M);
+    const int cnt = min(s_hi - s_lo, MERGE_TILE);
+    if (cnt == 0) return;
 
     const int32_t *sst = a.set_start + (size_t)slice * (a.cap_rows + 1);
     const int32_t *piv = a.pivot + (size_t)slice * a.cap_rows;
@@ -48,104 +94,128 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
     const T *Vs = V + (size_t)slice * a.N * HEAD_DIM;
     T *Ko = K_out + (size_t)slice * a.cap_rows * HEAD_DIM;
     T *Vo = V_out + (size_t)slice * a.cap_rows * HEAD_DIM;
-    float *wo = a.w_opt ? a.w_opt + (size_t)slice * a.N : nullptr;
+    float *wo = WITH_W ? a.w_opt + (size_t)slice * a.N : nullptr;
 
-    // lane i holds the first token of set s_lo+i (i <= cnt) and its pivot; entries are clamped
-    // into the slice so that inconsistent maps cannot address outside K and V
+    // lane i holds the first token of set s_lo+i and its pivot; entries are clamped into the
+    // slice so that inconsistent maps cannot address outside K and V
     int my_start = n, my_piv = 0;
-    if (lane <= cnt) my_start = min(max(sst[s_lo + lane], 0), n);
-    if (lane < cnt) my_piv = piv[s_lo + lane];
-    int my_len = __shfl_down(my_start, 1, WAVE) - my_start;       // lane i: |S_i| (garbage for i >= cnt)
-    const unsigned long long single_mask = __ballot(lane < cnt && my_len == 1);
+    if (lane < cnt) {
+        my_start = min(max(sst[s_lo + lane], 0), n);
+        my_piv = piv[s_lo + lane];
+    }
+    const int t_end = min(max(sst[s_lo + cnt], 0), n);               // end of the wave's last set
+    int my_next = __shfl_down(my_start, 1, WAVE);
+    if (lane == cnt - 1) my_next = t_end;
+    const unsigned long long single_mask = __ballot(lane < cnt && my_next - my_start == 1);
 
     int i = 0;
     while (i < cnt) {
-        // ---- runs of singleton sets: plain copy, up to four sets per step --------------------------
+        // ---- runs of singleton sets: plain copy, up to 4*U sets per step, all loads in flight ------
         if ((single_mask >> i) & 1ull) {
             int run = 1;
-            while (run < 4 && i + run < cnt && ((single_mask >> (i + run)) & 1ull)) ++run;
-            const int src = __shfl(my_start, i + min(slot, run - 1), WAVE);
-            if (slot < run) {
-                typename Elem<T>::Raw rk = Elem<T>::load(Ks + (size_t)src * HEAD_DIM, c);
-                typename Elem<T>::Raw rv = Elem<T>::load(Vs + (size_t)src * HEAD_DIM, c);
-                Elem<T>::store(Ko + (size_t)(s_lo + i + slot) * HEAD_DIM, c, rk);
-                Elem<T>::store(Vo + (size_t)(s_lo + i + slot) * HEAD_DIM, c, rv);
-                if (wo && c == 0) wo[src] = 1.f;
+            while (run < 4 * US && i + run < cnt && ((single_mask >> (i + run)) & 1ull)) ++run;
+            Raw rk[US], rv[US];
+            int src[US];
+#pragma unroll
+            for (int u = 0; u < US; ++u) {
+                const int r = 4 * u + slot;
+                src[u] = __shfl(my_start, i + min(r, run - 1), WAVE);
+                if (r < run) {
+                    rk[u] = E::load(Ks + (size_t)src[u] * HEAD_DIM, c);
+                    rv[u] = E::load(Vs + (size_t)src[u] * HEAD_DIM, c);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < US; ++u) {
+                const int r = 4 * u + slot;
+                if (r < run) {
+                    E::store(Ko + (size_t)(s_lo + i + r) * HEAD_DIM, c, rk[u]);
+                    E::store(Vo + (size_t)(s_lo + i + r) * HEAD_DIM, c, rv[u]);
+                    if (WITH_W && c == 0) wo[src[u]] = 1.f;
+                }
             }
             i += run;
             continue;
         }
         // ---- a set with several tokens --------------------------------------------------------------
         const int lo = __builtin_amdgcn_readlane(my_start, i);
-        const int hi = __builtin_amdgcn_readlane(my_start, i + 1);
+        const int hi = __builtin_amdgcn_readlane(my_next, i);
         const int m = hi - lo;
         if (m <= 0) { ++i; continue; }                                // inconsistent map: nothing to merge
         int p = __builtin_amdgcn_readlane(my_piv, i);
         p = min(max(p, lo), hi - 1);
+        const Raw kp_raw = E::load(Ks + (size_t)p * HEAD_DIM, c);
         float kp[8];
-        Elem<T>::to_float(Elem<T>::load(Ks + (size_t)p * HEAD_DIM, c), kp);
-
-        // first four rows stay in registers for the second sweep
-        float x0[8];
-        const bool v0 = lo + slot < hi;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x0[e] = 0.f;
-        if (v0) Elem<T>::to_float(Elem<T>::load(Ks + (size_t)(lo + slot) * HEAD_DIM, c), x0);
-
-        // sweep 1: distances to the pivot
-        float dsum = 0.f;
-        for (int j0 = lo; j0 < hi; j0 += 4) {
-            const int row = j0 + slot;
-            float x[8];
-            if (j0 == lo) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) x[e] = x0[e];
-            } else if (row < hi) {
-                Elem<T>::to_float(Elem<T>::load(Ks + (size_t)row * HEAD_DIM, c), x);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) x[e] = kp[e];
-            }
-            float sq = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { const float df = kp[e] - x[e]; sq = fmaf(df, df, sq); }
-            sq = row16_sum(sq);
-            dsum += row < hi ? sqrtf(sq) : 0.f;
-        }
-        dsum = rows4_sum(dsum);
-        // g_j = exp(-D_j^2 / (2 sigma^2)); with sigma = dsum / (sqrt(2) m) that is exp(-(D_j m / dsum)^2)
-        const float inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
-
-        // sweep 2: weights, weighted sums
-        float ak[8], av[8], gsum = 0.f;
+        float ak[8], av[8], gsum = 0.f, inv_mean = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) { ak[e] = 0.f; av[e] = 0.f; }
-        for (int j0 = lo; j0 < hi; j0 += 4) {
-            const int row = j0 + slot;
-            if (row < hi) {
+        // Rows past the end of the set are clamped to its last row and given weight zero, so
+        // that every lane runs the same straight-line code.
+        auto load_rows = [&](const T *base, int j0, Raw *r) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) r[u] = E::load(base + (size_t)min(j0 + 4 * u + slot, hi - 1) * HEAD_DIM, c);
+        };
+        auto distances = [&](int j0, const Raw *kr) {
+            float acc = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float x[8];
+                E::to_float(kr[u], x);
+                const float dist = __builtin_amdgcn_sqrtf(sq_dist16(kp, x));
+                acc += (j0 + 4 * u + slot < hi) ? dist : 0.f;
+            }
+            return acc;
+        };
+        // g_j = exp(-D_j^2 / (2 sigma^2)); with sigma = dsum / (sqrt(2) m) that is exp(-(D_j m / dsum)^2)
+        auto accumulate = [&](int j0, const Raw *kr, const Raw *vr) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = j0 + 4 * u + slot;
                 float x[8], v[8];
-                if (j0 == lo) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) x[e] = x0[e];
-                } else {
-                    Elem<T>::to_float(Elem<T>::load(Ks + (size_t)row * HEAD_DIM, c), x);
-                }
-                Elem<T>::to_float(Elem<T>::load(Vs + (size_t)row * HEAD_DIM, c), v);
-                float sq = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { const float df = kp[e] - x[e]; sq = fmaf(df, df, sq); }
-                sq = row16_sum(sq);
+                E::to_float(kr[u], x);
+                const float sq = sq_dist16(kp, x);
                 float g;
-                if (a.sigma_fixed) {
+                if (FIXED) {
                     g = __expf(-sq * a.inv_two_sigma_sq);
                 } else {
-                    const float r = sqrtf(sq) * inv_mean;
+                    const float r = __builtin_amdgcn_sqrtf(sq) * inv_mean;
                     g = __expf(-r * r);
                 }
+                g = row < hi ? g : 0.f;
                 gsum += g;
+                E::to_float(vr[u], v);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { ak[e] = fmaf(g, x[e], ak[e]); av[e] = fmaf(g, v[e], av[e]); }
-                if (wo && c == 0) wo[row] = g;
+                if (WITH_W && c == 0 && row < hi) wo[row] = g;
+            }
+        };
+
+        if (m <= 4 * U) {
+            // the whole set is read once: all loads issued together, both sweeps from registers
+            Raw k0[U], v0[U];
+            load_rows(Ks, lo, k0);
+            load_rows(Vs, lo, v0);
+            E::to_float(kp_raw, kp);
+            const float dsum = rows4_sum(distances(lo, k0));
+            inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
+            accumulate(lo, k0, v0);
+        } else {
+            // sweep 1: sum of the distances to the pivot
+            float dsum = 0.f;
+            for (int j0 = lo; j0 < hi; j0 += 4 * U) {
+                Raw kr[U];
+                load_rows(Ks, j0, kr);
+                if (j0 == lo) E::to_float(kp_raw, kp);
+                dsum += distances(j0, kr);
+            }
+            dsum = rows4_sum(dsum);
+            inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
+            // sweep 2: weights and weighted sums (K again, now from L2; V for the first time)
+            for (int j0 = lo; j0 < hi; j0 += 4 * U) {
+                Raw kr[U], vr[U];
+                load_rows(Ks, j0, kr);
+                load_rows(Vs, j0, vr);
+                accumulate(j0, kr, vr);
             }
         }
         gsum = rows4_sum(gsum);
@@ -156,9 +226,9 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
             ak[e] = rows4_sum(ak[e]) * inv_g;
             av[e] = rows4_sum(av[e]) * vscale;
         }
-        if (slot == 0) Elem<T>::store(Ko + (size_t)(s_lo + i) * HEAD_DIM, c, Elem<T>::from_float(ak));
-        if (slot == 1) Elem<T>::store(Vo + (size_t)(s_lo + i) * HEAD_DIM, c, Elem<T>::from_float(av));
-        if (wo && c == 0) {                                            // each writer normalises its own g_j
+        if (slot == 0) E::store(Ko + (size_t)(s_lo + i) * HEAD_DIM, c, E::from_float(ak));
+        if (slot == 1) E::store(Vo + (size_t)(s_lo + i) * HEAD_DIM, c, E::from_float(av));
+        if (WITH_W && c == 0) {                                        // each writer normalises its own g_j
             for (int row = lo + slot; row < hi; row += 4) wo[row] *= inv_g;
         }
         ++i;
@@ -169,14 +239,29 @@ template <typename T>
 static void launch_merge_t(const kvm_shape &sh, const void *K, const void *V, void *K_out, void *V_out,
                            const MergeArgs &a, hipStream_t st)
 {
-    const long long blocks = (long long)sh.B * sh.H_kv * a.blocks_per_slice;
-    hipLaunchKernelGGL(merge_kernel<T>, dim3((unsigned)blocks), dim3(MERGE_BLOCK), 0, st, (const T *)K, (const T *)V,
-                       (T *)K_out, (T *)V_out, a);
+    const long long blocks = (long long)sh.B * sh.H_kv * a.tiles_per_slice;
+    ProfScope prof("merge_kernel", st);
+    const dim3 grid((unsigned)blocks), block(MERGE_BLOCK);
+    const T *k = (const T *)K, *v = (const T *)V;
+    T *ko = (T *)K_out, *vo = (T *)V_out;
+    if (a.w_opt) {
+        if (a.sigma_fixed) hipLaunchKernelGGL((merge_kernel<T, true, true>), grid, block, 0, st, k, v, ko, vo, a);
+        else hipLaunchKernelGGL((merge_kernel<T, true, false>), grid, block, 0, st, k, v, ko, vo, a);
+    } else {
+        if (a.sigma_fixed) hipLaunchKernelGGL((merge_kernel<T, false, true>), grid, block, 0, st, k, v, ko, vo, a);
+        else hipLaunchKernelGGL((merge_kernel<T, false, false>), grid, block, 0, st, k, v, ko, vo, a);
+    }
+}
+
+size_t merge_workspace_bytes(const kvm_shape &sh)
+{
+    const size_t tiles = ((size_t)sh.N + MERGE_TILE - 1) / MERGE_TILE;
+    return (size_t)sh.B * sh.H_kv * (tiles + 1) * sizeof(int32_t);
 }
 
 kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
-                        void *V_out, float *w_opt, hipStream_t st)
+                        void *V_out, float *w_opt, int32_t *plan, hipStream_t st)
 {
     if ((long long)sh.B * sh.H_kv == 0 || cap_rows == 0 || sh.N == 0) return KVM_OK;
     MergeArgs a;
@@ -185,13 +270,21 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     a.n_sets = n_sets;
     a.seq_lens = sh.seq_lens;
     a.w_opt = w_opt;
+    a.plan = plan;
     a.H = sh.H_kv;
     a.N = sh.N;
     a.cap_rows = cap_rows;
-    a.blocks_per_slice = (cap_rows + MERGE_SETS_PER_BLOCK - 1) / MERGE_SETS_PER_BLOCK;
+    a.tiles_per_slice = (sh.N + MERGE_TILE - 1) / MERGE_TILE;
     a.sigma_fixed = pr.sigma_mode == KVM_SIGMA_FIXED;
     a.inv_two_sigma_sq = a.sigma_fixed ? 1.f / (2.f * pr.sigma * pr.sigma) : 0.f;
     a.value_scale = pr.value_scale_by_set_size;
+    {
+        ProfScope prof("merge_plan_kernel", st);
+        hipLaunchKernelGGL(merge_plan_kernel, dim3((unsigned)(sh.B * sh.H_kv)), dim3(PLAN_BLOCK), 0, st, set_start, n_sets,
+                           sh.seq_lens, plan, sh.H_kv, sh.N, cap_rows, a.tiles_per_slice);
+        kvm_status rc = check_launch("merge_plan_kernel");
+        if (rc != KVM_OK) return rc;
+    }
     switch (sh.dtype) {
     case KVM_F32: launch_merge_t<float>(sh, K, V, K_out, V_out, a, st); break;
     case KVM_F16: launch_merge_t<half_t>(sh, K, V, K_out, V_out, a, st); break;

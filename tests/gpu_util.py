@@ -76,7 +76,8 @@ def gpu_merge(K, V, dtype, params, set_start, pivot, n_sets, seq_lens=None, want
     Vo = torch.zeros((B, H, cap, d), dtype=TORCH_DT[dtype], device="cuda")
     w = torch.zeros((B, H, N), dtype=torch.float32, device="cuda") if want_w else None
     i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
-    kb.kvm_merge(sh, params, Kd, Vd, i32(set_start), i32(pivot), i32(n_sets), Ko, Vo, w, None)
+    ws = torch.empty(max(kb.kvm_workspace_bytes(sh, params), 256), dtype=torch.uint8, device="cuda")
+    kb.kvm_merge(sh, params, Kd, Vd, i32(set_start), i32(pivot), i32(n_sets), Ko, Vo, w, ws)
     torch.cuda.synchronize()
     return to_host_f64(Ko), to_host_f64(Vo), (None if w is None else w.cpu().numpy()), Ko, Vo
 

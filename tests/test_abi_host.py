@@ -88,12 +88,14 @@ def test_host_detectable_errors_return_before_any_launch():
     assert ident(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
     assert ident(_shape(), p, nbytes=8) == kb.KVM_ERR_WORKSPACE
 
-    def merge(sh, pr, K=one):
-        return lib.kvm_merge(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, one, None, None, 0, None)
+    def merge(sh, pr, K=one, ws=one, nbytes=1 << 30):
+        return lib.kvm_merge(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, one, None, ws, nbytes, None)
 
     assert merge(_shape(), kb.make_params(0.5, 0.1, 0.1, sigma_mode=kb.KVM_SIGMA_FIXED, sigma=0.0)) == kb.KVM_ERR_INVALID_ARG
     assert merge(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
     assert merge(_shape(d=256), p) == kb.KVM_ERR_UNSUPPORTED
+    assert merge(_shape(), p, ws=None) == kb.KVM_ERR_WORKSPACE
+    assert merge(_shape(), p, nbytes=4) == kb.KVM_ERR_WORKSPACE
 
 
 def test_binding_refuses_mismatched_tensors_on_the_host():
