@@ -12,7 +12,9 @@
 //                       accumulators all belong to one column, so the column sum needs no
 //                       cross-lane traffic until the very end and no atomics: deterministic.
 // The operand that sits in registers is the MFMA B operand in both kernels; the streamed
-// tile is the A operand, read from LDS with an XOR swizzle of its 16-byte chunks.
+// tile is the A operand.  Tiles go from global memory straight into a ring of LDS stages
+// (global_load_lds, no registers in between), several tiles ahead of the one being used,
+// with an XOR swizzle of their 16-byte chunks so that the fragment reads are conflict-free.
 #include "kvm_common.h"
 
 namespace kvm {
@@ -61,29 +63,47 @@ __device__ __forceinline__ int acc_row(int i, int lane) { return 8 * (i >> 2) + 
 // A streamed tile in LDS: TR rows of CHUNKS 16-byte chunks; chunk ch of row r sits at
 // position ch ^ (r mod CHUNKS), so that 16 lanes reading one chunk column of 16
 // consecutive rows hit 16 different bank groups.
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+constexpr int ATT_STAGES = 2;            // LDS stages of the streamed operand
+constexpr int ATT_MIN_BLOCKS = 3;        // workgroups per CU the register budget is held to (3 waves per SIMD)
+
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters at max)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for
+// every outstanding global_load_lds, i.e. for the tiles that are meant to stay in flight.
+// The LDS data a step needs is waited for explicitly with wait_vmcnt before the barrier.
+__device__ __forceinline__ void barrier_no_fence() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <typename T> struct Tile {
     static constexpr int CH = Mma<T>::CHUNKS;
     static constexpr int TR = 32 * Mma<T>::NBLK;
-    static constexpr int PER_THREAD = TR * CH / ATT_BLOCK;
+    static constexpr int SLOTS = TR * CH;                     // 16-byte slots per stage
+    static constexpr int PER_THREAD = SLOTS / ATT_BLOCK;      // global_load_lds instructions per wave and tile
     static __device__ __forceinline__ int lds_index(int row, int ch) { return row * CH + (ch ^ (row & (CH - 1))); }
 
-    // rows [row0, row0+TR) of a (N x 128) matrix; rows >= n_valid read as zero
-    static __device__ __forceinline__ void load(const T *base, int row0, int n_valid, u32x4 *regs) {
+    // Rows [row0, row0+TR) of an (N x 128) matrix -> one LDS stage, asynchronously.  One
+    // instruction fills 64 consecutive slots (lane l -> slot base + l), so the swizzle is
+    // applied on the source side: the lane that fills slot (row, pos) fetches chunk
+    // pos ^ (row mod CH).  Rows >= n_valid are replaced by row n_valid-1 (finite data whose
+    // scores are masked or weighted by zero later); nothing outside [0, n_valid) is read.
+    static __device__ __forceinline__ void issue(const T *base, int row0, int n_valid, u32x4 *stage, int wave, int lane) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
-            const int id = threadIdx.x + ATT_BLOCK * i;
-            const int row = id / CH, ch = id % CH;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (row0 + row < n_valid)
-                v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base + (size_t)(row0 + row) * HEAD_DIM) + ch * 16);
-            regs[i] = v;
-        }
-    }
-    static __device__ __forceinline__ void store(u32x4 *lds, const u32x4 *regs) {
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int id = threadIdx.x + ATT_BLOCK * i;
-            lds[lds_index(id / CH, id % CH)] = regs[i];
+            const int slot0 = (wave * PER_THREAD + i) * 64;
+            const int row = slot0 / CH + lane / CH;
+            const int pos = lane % CH;
+            const int src_row = min(row0 + row, n_valid - 1);
+            const char *src = reinterpret_cast<const char *>(base + (size_t)src_row * HEAD_DIM) + ((pos ^ (row & (CH - 1))) * 16);
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + slot0), 16, 0, 0);
         }
     }
     // fragment f of 32-row block blk for this lane (MFMA A operand)
@@ -122,20 +142,102 @@ __device__ __forceinline__ TileMap map_block(int n_slices, int tiles_per_slice) 
 }
 
 // ------------------------------------------------------------------------------------------
+// per-block reductions
+//
+// A wave issues at most one instruction every other issue slot of its SIMD, so the vector
+// ALU and the matrix pipe only stay busy with about four waves per SIMD.  The kernels are
+// therefore written to fit 128 registers (64 of them hold the stationary operand): one
+// accumulator block at a time, fragments fetched four at a time, and the overlap of MFMA,
+// exp2 and LDS traffic is left to the hardware interleaving the waves.
+// ------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float max16(const f32x16 &v) {
+    const float a = fmaxf(fmaxf(v[0], v[1]), v[2]), b = fmaxf(fmaxf(v[3], v[4]), v[5]);
+    const float c = fmaxf(fmaxf(v[6], v[7]), v[8]), d = fmaxf(fmaxf(v[9], v[10]), v[11]);
+    const float e = fmaxf(fmaxf(v[12], v[13]), v[14]);
+    return fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), fmaxf(e, v[15]));
+}
+
+// pass 1: the online (max, sum) of a row absorbs 16 more scores (-inf = masked)
+__device__ __forceinline__ void rowstat_update(const f32x16 &acc, float c, float &m_run, float &l_run) {
+    const float m_new = fmaxf(m_run, max16(acc));
+    const float mc = m_new > -INFINITY ? m_new * c : 0.f;     // nothing seen yet: any finite reference works
+    float p0 = 0.f, p1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        p0 += __builtin_amdgcn_exp2f(fmaf(acc[i], c, -mc));
+        p1 += __builtin_amdgcn_exp2f(fmaf(acc[i + 1], c, -mc));
+    }
+    l_run = l_run * __builtin_amdgcn_exp2f(m_run * c - mc) + (p0 + p1);
+    m_run = m_new;
+}
+
+// pass 2: part[0..1] += exp2(c * acc - L) with L read from the tile's row statistics in LDS
+// (accumulator i of lane l is row 8*(i/4) + 4*(l/32) + i%4 of the 32-row block)
+__device__ __forceinline__ void colsum_update(const f32x16 &acc, const float *lse_tile, int blk, int lane, float c, float *part) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const f32x4 L = *reinterpret_cast<const f32x4 *>(&lse_tile[32 * blk + 8 * r + 4 * (lane >> 5)]);
+        part[0] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r], c, -L[0]));
+        part[1] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 1], c, -L[1]));
+        part[0] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 2], c, -L[2]));
+        part[1] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 3], c, -L[3]));
+    }
+}
+
+constexpr int FRAG_BATCH = 2;            // A fragments fetched from LDS per batch of MFMAs (generic path)
+
+// one 32x32 block of scores: A fragments from the LDS tile, B fragments from registers
+template <typename T>
+__device__ __forceinline__ f32x16 score_block(const u32x4 *tile, int blk, const u32x4 *bfrag, int lane) {
+    using M = Mma<T>;
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int f0 = 0; f0 < M::FRAGS; f0 += FRAG_BATCH) {
+        u32x4 a[FRAG_BATCH];
+#pragma unroll
+        for (int f = 0; f < FRAG_BATCH; ++f) a[f] = Tile<T>::frag(tile, blk, f0 + f, lane);
+#pragma unroll
+        for (int f = 0; f < FRAG_BATCH; ++f) M::mma(acc, a[f], bfrag[f0 + f]);
+    }
+    return acc;
+}
+
+// Unmasked tiles (16-bit types): the 8 A fragments of a 32-row block are fetched once, all
+// reads in flight together, and serve both stationary blocks of the wave.
+template <typename T>
+__device__ __forceinline__ void load_frags8(const u32x4 *tile, int blk, int lane, u32x4 *a) {
+#pragma unroll
+    for (int f = 0; f < 8; ++f) a[f] = Tile<T>::frag(tile, blk, f, lane);
+}
+
+template <typename T>
+__device__ __forceinline__ f32x16 score_block8(const u32x4 *a, const u32x4 *bfrag) {
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int f = 0; f < 8; ++f) Mma<T>::mma(acc, a[f], bfrag[f]);
+    return acc;
+}
+
+// ------------------------------------------------------------------------------------------
 // pass 1: row log-sum-exp
 // ------------------------------------------------------------------------------------------
 
 template <typename T>
-__global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                  float *__restrict__ lse, const int32_t *__restrict__ seq_lens,
-                                                                 int n_qslices, int HG, int G, int N, int tiles_per_slice,
-                                                                 float c)
+                                                                 int n_qslices, int HG, int G, int N, int n_pad,
+                                                                 int tiles_per_slice, float c)
 {
     using M = Mma<T>;
     using TL = Tile<T>;
     constexpr int NB = M::NBLK, TR = TL::TR;
     constexpr int ROWS_PER_BLOCK = ATT_WAVES * 32 * NB;       // query rows of a workgroup
-    __shared__ u32x4 lds[2][TR * M::CHUNKS];
+    __shared__ u32x4 lds[ATT_STAGES][TL::SLOTS];
 
     const TileMap tm = map_block(n_qslices, tiles_per_slice);
     if (!tm.valid) return;
@@ -146,10 +248,18 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restr
     const int n = clamp_len(seq_lens, b, N);
     const int q_begin = tile * ROWS_PER_BLOCK;
     if (q_begin >= n) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar: per-wave branches stay scalar
     const T *Qs = Q + (size_t)qslice * N * HEAD_DIM;
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
     const int q0 = q_begin + wave * 32 * NB;                  // first query row of this wave
+
+    const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
+    const int steps = q_last / TR + 1;                        // key tiles 0 .. steps-1
+    // tiles 0 .. STAGES-2 start their way into LDS; tile indices past the end are clamped so
+    // that every step issues the same number of loads (the waits below count instructions)
+#pragma unroll
+    for (int t = 0; t < ATT_STAGES - 1; ++t) TL::issue(Ks, min(t, steps - 1) * TR, n, lds[t], wave, lane);
 
     u32x4 qf[NB][M::FRAGS];
 #pragma unroll
@@ -159,15 +269,34 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restr
 #pragma unroll
     for (int qb = 0; qb < NB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
-    const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
-    const int steps = q_last / TR + 1;                        // key tiles 0 .. steps-1
-    u32x4 pre[TL::PER_THREAD];
-    TL::load(Ks, 0, n, pre);
-    TL::store(lds[0], pre);
-    __syncthreads();
     for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < steps) TL::load(Ks, (s + 1) * TR, n, pre);
+        const u32x4 *cur = lds[s % ATT_STAGES];
+        // this thread's part of tile s has landed once at most the loads of the STAGES-2 later
+        // tiles are outstanding; after the barrier everybody's part has, and everybody is done
+        // with the stage that tile s+STAGES-1 now overwrites
+        wait_vmcnt<(ATT_STAGES - 2) * TL::PER_THREAD>();
+        barrier_no_fence();
+        TL::issue(Ks, min(s + ATT_STAGES - 1, steps - 1) * TR, n, lds[(s + ATT_STAGES - 1) % ATT_STAGES], wave, lane);
+        if constexpr (NB == 2) {
+            if (s * TR + TR - 1 <= q0) {
+                // every key of the tile precedes every query of this wave: four full blocks
+                u32x4 a[8];
+                load_frags8<T>(cur, 0, lane, a);
+                f32x16 acc = score_block8<T>(a, qf[0]);
+                rowstat_update(acc, c, m_run[0], l_run[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[1]);
+                load_frags8<T>(cur, 1, lane, a);              // in flight during the reduction below
+                rowstat_update(acc, c, m_run[1], l_run[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[0]);
+                rowstat_update(acc, c, m_run[0], l_run[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[1]);
+                rowstat_update(acc, c, m_run[1], l_run[1]);
+                continue;
+            }
+        }
 #pragma unroll
         for (int kb = 0; kb < NB; ++kb) {
             const int key0 = s * TR + 32 * kb;
@@ -175,11 +304,7 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restr
             for (int qb = 0; qb < NB; ++qb) {
                 const int qrow0 = q0 + 32 * qb;
                 if (key0 > qrow0 + 31) continue;             // every key of the block is in the future
-                f32x16 acc;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-                for (int f = 0; f < M::FRAGS; ++f) M::mma(acc, TL::frag(lds[buf], kb, f, lane), qf[qb][f]);
+                f32x16 acc = score_block<T>(cur, kb, qf[qb], lane);
                 // acc[i]: key = key0 + acc_row(i), query = qrow0 + lane%32
                 if (key0 + 31 > qrow0) {
                     const int q = qrow0 + (lane & 31);
@@ -187,24 +312,13 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restr
                     for (int i = 0; i < 16; ++i)
                         if (key0 + acc_row(i, lane) > q) acc[i] = -INFINITY;
                 }
-                float tmax = acc[0];
-#pragma unroll
-                for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
-                const float m_new = fmaxf(m_run[qb], tmax);
-                if (m_new > -INFINITY) {
-                    const float mc = m_new * c;
-                    float sum = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[i], c, -mc));
-                    l_run[qb] = l_run[qb] * __builtin_amdgcn_exp2f(m_run[qb] * c - mc) + sum;
-                    m_run[qb] = m_new;
-                }
+                rowstat_update(acc, c, m_run[qb], l_run[qb]);
             }
         }
-        if (s + 1 < steps) TL::store(lds[buf ^ 1], pre);
-        __syncthreads();
     }
-    // lanes l and l+32 hold the two halves of a row's keys
+    wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
+    // lanes l and l+32 hold the two halves of a row's keys; rows in [n, n_pad) get +inf so
+    // that the second pass weighs them with exp2(-inf) = 0
 #pragma unroll
     for (int qb = 0; qb < NB; ++qb) {
         const float m_o = __shfl_xor(m_run[qb], 32, WAVE), l_o = __shfl_xor(l_run[qb], 32, WAVE);
@@ -213,7 +327,7 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restr
         if (m_run[qb] > -INFINITY) l += l_run[qb] * __builtin_amdgcn_exp2f((m_run[qb] - m) * c);
         if (m_o > -INFINITY) l += l_o * __builtin_amdgcn_exp2f((m_o - m) * c);
         const int q = q0 + 32 * qb + (lane & 31);
-        if (lane < 32 && q < n) lse[(size_t)qslice * N + q] = m * c + __log2f(l);
+        if (lane < 32 && q < n_pad) lse[(size_t)qslice * n_pad + q] = q < n ? m * c + __log2f(l) : INFINITY;
     }
 }
 
@@ -222,24 +336,25 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_lse_kernel(const T *__restr
 // ------------------------------------------------------------------------------------------
 
 template <typename T>
-__global__ __launch_bounds__(ATT_BLOCK, 2) void attn_colsum_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const float *__restrict__ lse, float *__restrict__ mass,
                                                                     const int32_t *__restrict__ seq_lens, int n_kvslices,
-                                                                    int H, int G, int N, int tiles_per_slice, float c)
+                                                                    int H, int G, int N, int n_pad, int tiles_per_slice, float c)
 {
     using M = Mma<T>;
     using TL = Tile<T>;
     constexpr int NB = M::NBLK, TR = TL::TR;
     constexpr int KEYS_PER_BLOCK = ATT_WAVES * 32 * NB;
-    __shared__ u32x4 lds[2][TR * M::CHUNKS];
-    __shared__ __attribute__((aligned(16))) float lds_lse[2][TR];
+    __shared__ u32x4 lds[ATT_STAGES][TL::SLOTS];
+    __shared__ __attribute__((aligned(16))) float lds_lse[ATT_STAGES][64];
 
     const TileMap tm = map_block(n_kvslices, tiles_per_slice);
     if (!tm.valid) return;
     const int kvslice = tm.slice, tile = tm.tile;             // tile 0 has the most rows below it
     const int b = kvslice / H, h = kvslice % H;
     const int n = clamp_len(seq_lens, b, N);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar: per-wave branches stay scalar
     const int k_begin = tile * KEYS_PER_BLOCK;
     const int k0 = k_begin + wave * 32 * NB;
     float *mass_s = mass + (size_t)kvslice * N;
@@ -249,84 +364,82 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_colsum_kernel(const T *__re
     }
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
 
+    const int first = k_begin / TR;                           // first query tile that sees these keys
+    const int last = (n - 1) / TR;
+    const int steps_per_head = last - first + 1;
+    const int steps = steps_per_head * G;
+    // tile t of the sequence (g, qt): Q rows and their statistics -> LDS; every wave issues the
+    // (identical) statistics load so that all waves count the same number of instructions
+    auto issue = [&](int t) {
+        t = min(t, steps - 1);
+        const int g = t / steps_per_head, qt = first + t % steps_per_head;
+        const size_t qslice = (size_t)b * H * G + (size_t)h * G + g;
+        TL::issue(Q + qslice * N * HEAD_DIM, qt * TR, n, lds[t % ATT_STAGES], wave, lane);
+        if (lane < TR)
+            __builtin_amdgcn_global_load_lds((gptr_t)(lse + qslice * n_pad + qt * TR + lane), (lptr_t)lds_lse[t % ATT_STAGES], 4, 0, 0);
+    };
+#pragma unroll
+    for (int t = 0; t < ATT_STAGES - 1; ++t) issue(t);
     u32x4 kf[NB][M::FRAGS];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) load_stationary<T>(Ks, k0 + 32 * kb, n, lane, kf[kb]);
 
     float colsum[NB];
+    float part[NB][2];
 #pragma unroll
-    for (int kb = 0; kb < NB; ++kb) colsum[kb] = 0.f;
-
-    const int first = k_begin / TR;                           // first query tile that sees these keys
-    const int last = (n - 1) / TR;
-    const int steps_per_head = last - first + 1;
-    const int steps = steps_per_head * G;
-    u32x4 pre[TL::PER_THREAD];
-    float pre_lse = 0.f;
-
-    auto prefetch = [&](int s) {
-        const int g = s / steps_per_head, qt = first + s % steps_per_head;
-        const size_t qslice = (size_t)b * H * G + (size_t)h * G + g;
-        TL::load(Q + qslice * N * HEAD_DIM, qt * TR, n, pre);
-        if (threadIdx.x < TR) {
-            const int t = qt * TR + threadIdx.x;
-            pre_lse = t < n ? lse[qslice * N + t] : INFINITY; // exp2(-inf) = 0: padded rows add nothing
-        }
-    };
-    auto commit = [&](int buf) {
-        TL::store(lds[buf], pre);
-        if (threadIdx.x < TR) lds_lse[buf][threadIdx.x] = pre_lse;
-    };
-
-    prefetch(0);
-    commit(0);
-    __syncthreads();
+    for (int kb = 0; kb < NB; ++kb) part[kb][0] = part[kb][1] = 0.f;
+    int qt = first - 1;
     for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        const int qt = first + s % steps_per_head;
-        if (s + 1 < steps) prefetch(s + 1);
+        const u32x4 *cur = lds[s % ATT_STAGES];
+        const float *cur_lse = lds_lse[s % ATT_STAGES];
+        qt = qt == last ? first : qt + 1;                     // query tile of step s (the heads follow one another)
+        wait_vmcnt<(ATT_STAGES - 2) * (TL::PER_THREAD + 1)>();
+        barrier_no_fence();
+        issue(s + ATT_STAGES - 1);
+        if constexpr (NB == 2) {
+            if (qt * TR >= k0 + 32 * NB - 1) {
+                // every query of the tile follows every key of this wave: four full blocks
+                // (the fences keep the scheduler from hoisting later blocks' LDS reads, which
+                // would not fit the register budget)
+                u32x4 a[8];
+                load_frags8<T>(cur, 0, lane, a);
+                f32x16 acc = score_block8<T>(a, kf[0]);
+                colsum_update(acc, cur_lse, 0, lane, c, part[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, kf[1]);
+                load_frags8<T>(cur, 1, lane, a);              // in flight during the reduction below
+                colsum_update(acc, cur_lse, 0, lane, c, part[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, kf[0]);
+                colsum_update(acc, cur_lse, 1, lane, c, part[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, kf[1]);
+                colsum_update(acc, cur_lse, 1, lane, c, part[1]);
+                continue;
+            }
+        }
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb) {
             const int qrow0 = qt * TR + 32 * qb;
-            float L[16];
-            bool have_L = false;
 #pragma unroll
             for (int kb = 0; kb < NB; ++kb) {
                 const int key0 = k0 + 32 * kb;
                 if (qrow0 + 31 < key0) continue;             // every query of the block precedes the keys
-                if (!have_L) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const f32x4 v = *reinterpret_cast<const f32x4 *>(&lds_lse[buf][32 * qb + 8 * r + 4 * (lane >> 5)]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) L[4 * r + e] = v[e];
-                    }
-                    have_L = true;
-                }
-                f32x16 acc;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-                for (int f = 0; f < M::FRAGS; ++f) M::mma(acc, TL::frag(lds[buf], qb, f, lane), kf[kb][f]);
+                f32x16 acc = score_block<T>(cur, qb, kf[kb], lane);
                 // acc[i]: query = qrow0 + acc_row(i), key = key0 + lane%32
-                float part[4] = {0.f, 0.f, 0.f, 0.f};
                 if (qrow0 < key0 + 31) {                      // block touches the diagonal
                     const int key = key0 + (lane & 31);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(acc[i], c, -L[i]));
-                        part[i & 3] += (qrow0 + acc_row(i, lane) >= key) ? p : 0.f;
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) part[i & 3] += __builtin_amdgcn_exp2f(fmaf(acc[i], c, -L[i]));
+                    for (int i = 0; i < 16; ++i)
+                        if (qrow0 + acc_row(i, lane) < key) acc[i] = -INFINITY;
                 }
-                colsum[kb] += (part[0] + part[1]) + (part[2] + part[3]);
+                colsum_update(acc, cur_lse, qb, lane, c, part[kb]);
             }
         }
-        if (s + 1 < steps) commit(buf ^ 1);
-        __syncthreads();
     }
+    wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb) colsum[kb] = part[kb][0] + part[kb][1];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) {
         const float total = colsum[kb] + __shfl_xor(colsum[kb], 32, WAVE);
@@ -339,6 +452,8 @@ __global__ __launch_bounds__(ATT_BLOCK, 2) void attn_colsum_kernel(const T *__re
 // host launcher
 // ------------------------------------------------------------------------------------------
 
+int attn_lse_stride(int N);
+
 template <typename T>
 static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse, hipStream_t st)
 {
@@ -346,11 +461,12 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
     const int tiles = (sh.N + ROWS - 1) / ROWS;
     const float c = (float)(1.4426950408889634 / sqrt((double)sh.d));
     const int n_q = sh.B * sh.H_kv * sh.G, n_kv = sh.B * sh.H_kv;
+    const int n_pad = attn_lse_stride(sh.N);
     {
         const long long blocks = (long long)((n_q + 7) / 8) * 8 * tiles;
         ProfScope prof("attn_lse_kernel", st);
         hipLaunchKernelGGL(attn_lse_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q, (const T *)K,
-                           lse, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, tiles, c);
+                           lse, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, c);
         kvm_status rc = check_launch("attn_lse_kernel");
         if (rc != KVM_OK) return rc;
     }
@@ -358,10 +474,13 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
         const long long blocks = (long long)((n_kv + 7) / 8) * 8 * tiles;
         ProfScope prof("attn_colsum_kernel", st);
         hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
-                           (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, tiles, c);
+                           (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, c);
         return check_launch("attn_colsum_kernel");
     }
 }
+
+// Row statistics are stored with the sequence length rounded up to a whole streamed tile.
+int attn_lse_stride(int N) { return (N + 63) / 64 * 64; }
 
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse, hipStream_t st)
 {

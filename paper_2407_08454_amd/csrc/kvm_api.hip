@@ -106,7 +106,10 @@ static int capacity(const kvm_shape *sh, const kvm_params *pr)
     return pr->enforce_budget ? (int)floor(pr->budget * (double)sh->N) : sh->N;
 }
 
-static size_t ws_attn(const kvm_shape *sh) { return align_up((size_t)sh->B * sh->H_kv * sh->G * sh->N * sizeof(float), 256); }
+static size_t ws_attn(const kvm_shape *sh)
+{
+    return align_up((size_t)sh->B * sh->H_kv * sh->G * attn_lse_stride(sh->N) * sizeof(float), 256);
+}
 static size_t ws_identify(const kvm_shape *sh)
 {
     const size_t tok = (size_t)sh->B * sh->H_kv * sh->N;

@@ -154,5 +154,6 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
                         const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
                         void *V_out, float *w_opt, int32_t *plan, hipStream_t st);
 size_t merge_workspace_bytes(const kvm_shape &sh);
+int attn_lse_stride(int N);
 
 }  // namespace kvm
