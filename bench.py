@@ -24,6 +24,16 @@ PEAK_MFMA = {"f16": 2.5e15, "bf16": 2.5e15, "f32": 157.3e12}   # dense matrix pe
 PEAK_HBM = 8.0e12                                               # B/s
 METRIC = "KV tokens compressed/sec (all layers x heads) at Llama2-7B N=4096"
 
+# HBM bytes per launch (read, written) on the headline workload (--config 2, all layers, budget 0.5),
+# from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (hardware counters cannot
+# be read from inside this process; re-measure after a kernel change).
+MEASURED_TRAFFIC = {
+    "attn_lse_kernel": (2485719100, 16777216),
+    "attn_colsum_kernel": (6034485516, 67108864),
+    "cosine_scan_kernel": (1140774876, 26957333),
+    "merge_kernel": (2334026860, 676896256),
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -33,8 +43,12 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload id (2 = the headline Llama2-7B shape)")
     ap.add_argument("--layers", type=int, default=None, help="generate only this many layers (not the headline run)")
     ap.add_argument("--budget", type=float, default=0.5)
-    ap.add_argument("--cpu-slices", type=int, default=64, help="slices the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-slices", type=int, default=512, help="slices the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
+    ap.add_argument("--gen-workers", type=int, default=None,
+                    help="processes that generate the inputs (1 = in this process, e.g. under a profiler)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of K before the timed region (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (slices are independent; see DESIGN.md for how it "
@@ -49,7 +63,7 @@ def main() -> int:
     cfg = synth.CONFIGS[args.config]
     dtype = cfg["dtype"]
     t0 = time.time()
-    Q, K, V, lens = synth.gen_config(cfg, layers=args.layers)
+    Q, K, V, lens = synth.gen_config(cfg, layers=args.layers, workers=args.gen_workers)
     gen_s = time.time() - t0
     B, H, G, N, d = K.shape[0], cfg["H_kv"], cfg["G"], cfg["N"], cfg["d"]
     n_per_b = np.full(B, N, np.int64) if lens is None else lens.astype(np.int64)
@@ -72,6 +86,11 @@ def main() -> int:
     for _ in range(args.warmup):
         kb.compress(shape, params, Qd, Kd, Vd, buf)
     torch.cuda.synchronize()
+    if args.calibration_copy:          # reads and writes K.numel() * element_size bytes exactly once
+        copy = torch.empty_like(Kd)
+        copy.copy_(Kd)
+        torch.cuda.synchronize()
+        del copy
 
     if not args.no_profile:
         kb.kvm_profile_enable(8 * args.steps)
@@ -108,21 +127,27 @@ def main() -> int:
     bytes_merge = float(2 * token_slices * d * esz + 2 * M_total * d * esz + 8 * M_total)
     roofline = None
     hbm = {}
+    headline = args.config == 2 and args.layers is None and args.budget == 0.5
+
+    def traffic(name):
+        return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None
+
     if kernels:
         dom = max(kernels, key=kernels.get)
         if dom.startswith("attn"):
             ach = flops_attn / (kernels[dom] * 1e-3)
             roofline = {"kernel": dom, "bound": "mfma", "achieved": ach / 1e12, "peak": PEAK_MFMA[dtype] / 1e12,
-                        "unit": "TFLOP/s", "frac": ach / PEAK_MFMA[dtype], "traffic": None,
-                        "ms_per_launch": kernels[dom]}
+                        "unit": "TFLOP/s", "frac": ach / PEAK_MFMA[dtype], "traffic": traffic(dom),
+                        "algorithmic_flops": flops_attn, "ms_per_launch": kernels[dom]}
         else:
             byts = bytes_merge if dom == "merge_kernel" else bytes_cos
             ach = byts / (kernels[dom] * 1e-3)
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                        "frac": ach / PEAK_HBM, "traffic": None, "ms_per_launch": kernels[dom]}
+                        "frac": ach / PEAK_HBM, "traffic": traffic(dom), "algorithmic_bytes": byts,
+                        "ms_per_launch": kernels[dom]}
         for name, byts in (("cosine_scan_kernel", bytes_cos), ("merge_kernel", bytes_merge)):
             if name in kernels:
-                hbm[name] = {"algorithmic_GB": byts / 1e9, "ms": kernels[name],
+                hbm[name] = {"algorithmic_GB": byts / 1e9, "traffic": traffic(name), "ms": kernels[name],
                              "GB/s": byts / (kernels[name] * 1e-3) / 1e9,
                              "frac_of_hbm_peak": byts / (kernels[name] * 1e-3) / PEAK_HBM}
 

@@ -172,6 +172,8 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
  *               round-to-nearest-even to dtype.
  *   w_opt       out  (B, H_kv, N) float32 or NULL: key weight of every token
  *               (positions not covered by a stored set are not written)
+ *   ws          the work plan (first set of every 64-token tile of a slice) is
+ *               built there before the merge kernel runs
  */
 kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
                      const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,

@@ -414,3 +414,26 @@ def test_whole_pass_config5_ragged_batch():
                     "config 5")
     for b, n in enumerate(lens):
         assert (g["n_sets"][b] <= math.floor(0.35 * n)).all()
+
+
+def test_whole_pass_config2_full_size_sampled():
+    """The headline workload whole (1024 slices in one launch of every kernel, as the benchmark
+    times it): the oracle on a spread sample of slices, size-independent properties on all."""
+    cfg = synth.CONFIGS[2]
+    L, H, N = cfg["layers"], cfg["H_kv"], cfg["N"]
+    _say(f"whole pass: config 2 at full size ({L} layers x {H} heads)")
+    Q, K, V, lens = synth.gen_config(cfg)
+    sample = [(0, 0), (L - 1, H - 1), (7, 13), (16, 5), (21, 30), (30, 1)]
+    params = kb.kvm_params_for_budget(0.5)
+    g = _whole_pass(Q, K, V, "f16", 1, params, lens, sample, "config 2 full")
+    assert g["n_sets"].shape == (L, H) and (g["n_sets"] <= N // 2).all() and (g["n_sets"] > 0).all()
+    assert (g["status"] == 0).all()
+    # every attention row sums to one, so a slice's scores sum to its length
+    Kd = gu.to_dev(K, "f16")
+    sh = kb.make_shape(Kd, 1, None)
+    mass = torch.empty((L, H, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(kb.kvm_workspace_bytes(sh, params), dtype=torch.uint8, device="cuda")
+    kb.kvm_attn_mass(sh, gu.to_dev(Q, "f16"), Kd, mass, ws)
+    tot = mass.double().sum(-1).cpu().numpy()
+    assert np.abs(tot / N - 1).max() <= 1e-5, f"scores of a slice do not sum to n: {np.abs(tot / N - 1).max():.2e}"
+    assert (mass[:, :, 0] >= 1).all() and (mass[:, :, N - 1] <= 1).all() and (mass > 0).all()
