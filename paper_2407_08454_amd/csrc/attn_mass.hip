@@ -66,7 +66,6 @@ __device__ __forceinline__ int acc_row(int i, int lane) { return 8 * (i >> 2) + 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-constexpr int ATT_STAGES = 2;            // LDS stages of the streamed operand
 constexpr int ATT_MIN_BLOCKS = 3;        // workgroups per CU the register budget is held to (3 waves per SIMD)
 
 // s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters at max)
@@ -237,7 +236,9 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     using TL = Tile<T>;
     constexpr int NB = M::NBLK, TR = TL::TR;
     constexpr int ROWS_PER_BLOCK = ATT_WAVES * 32 * NB;       // query rows of a workgroup
-    __shared__ u32x4 lds[ATT_STAGES][TL::SLOTS];
+    // one LDS object per stage: the compiler then knows that the fragment reads of a step do
+    // not touch the stage the next tile is being loaded into, and does not wait for that load
+    __shared__ u32x4 lds_a[TL::SLOTS], lds_b[TL::SLOTS];
 
     const TileMap tm = map_block(n_qslices, tiles_per_slice);
     if (!tm.valid) return;
@@ -256,10 +257,9 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
 
     const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
     const int steps = q_last / TR + 1;                        // key tiles 0 .. steps-1
-    // tiles 0 .. STAGES-2 start their way into LDS; tile indices past the end are clamped so
-    // that every step issues the same number of loads (the waits below count instructions)
-#pragma unroll
-    for (int t = 0; t < ATT_STAGES - 1; ++t) TL::issue(Ks, min(t, steps - 1) * TR, n, lds[t], wave, lane);
+    // tile 0 starts its way into LDS; tile indices past the end are clamped so that every step
+    // issues the same number of loads (the waits below count instructions)
+    TL::issue(Ks, 0, n, lds_a, wave, lane);
 
     u32x4 qf[NB][M::FRAGS];
 #pragma unroll
@@ -269,14 +269,12 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
 #pragma unroll
     for (int qb = 0; qb < NB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
-    for (int s = 0; s < steps; ++s) {
-        const u32x4 *cur = lds[s % ATT_STAGES];
-        // this thread's part of tile s has landed once at most the loads of the STAGES-2 later
-        // tiles are outstanding; after the barrier everybody's part has, and everybody is done
-        // with the stage that tile s+STAGES-1 now overwrites
-        wait_vmcnt<(ATT_STAGES - 2) * TL::PER_THREAD>();
+    auto step = [&](int s, const u32x4 *cur, u32x4 *nxt) {
+        // this thread's part of tile s has landed; after the barrier everybody's part has, and
+        // everybody is done with the stage that tile s+1 now overwrites
+        wait_vmcnt<0>();
         barrier_no_fence();
-        TL::issue(Ks, min(s + ATT_STAGES - 1, steps - 1) * TR, n, lds[(s + ATT_STAGES - 1) % ATT_STAGES], wave, lane);
+        TL::issue(Ks, min(s + 1, steps - 1) * TR, n, nxt, wave, lane);
         if constexpr (NB == 2) {
             if (s * TR + TR - 1 <= q0) {
                 // every key of the tile precedes every query of this wave: four full blocks
@@ -294,7 +292,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, qf[1]);
                 rowstat_update(acc, c, m_run[1], l_run[1]);
-                continue;
+                return;
             }
         }
 #pragma unroll
@@ -315,6 +313,10 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
                 rowstat_update(acc, c, m_run[qb], l_run[qb]);
             }
         }
+    };
+    for (int s = 0; s < steps; s += 2) {
+        step(s, lds_a, lds_b);
+        if (s + 1 < steps) step(s + 1, lds_b, lds_a);
     }
     wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
     // lanes l and l+32 hold the two halves of a row's keys; rows in [n, n_pad) get +inf so
@@ -345,8 +347,10 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     using TL = Tile<T>;
     constexpr int NB = M::NBLK, TR = TL::TR;
     constexpr int KEYS_PER_BLOCK = ATT_WAVES * 32 * NB;
-    __shared__ u32x4 lds[ATT_STAGES][TL::SLOTS];
-    __shared__ __attribute__((aligned(16))) float lds_lse[ATT_STAGES][64];
+    // one LDS object per stage: the compiler then knows that the fragment reads of a step do
+    // not touch the stage the next tile is being loaded into, and does not wait for that load
+    __shared__ u32x4 lds_a[TL::SLOTS], lds_b[TL::SLOTS];
+    __shared__ __attribute__((aligned(16))) float lse_a[64], lse_b[64];
 
     const TileMap tm = map_block(n_kvslices, tiles_per_slice);
     if (!tm.valid) return;
@@ -370,16 +374,15 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     const int steps = steps_per_head * G;
     // tile t of the sequence (g, qt): Q rows and their statistics -> LDS; every wave issues the
     // (identical) statistics load so that all waves count the same number of instructions
-    auto issue = [&](int t) {
+    auto issue = [&](int t, u32x4 *stage, float *stage_lse) {
         t = min(t, steps - 1);
         const int g = t / steps_per_head, qt = first + t % steps_per_head;
         const size_t qslice = (size_t)b * H * G + (size_t)h * G + g;
-        TL::issue(Q + qslice * N * HEAD_DIM, qt * TR, n, lds[t % ATT_STAGES], wave, lane);
+        TL::issue(Q + qslice * N * HEAD_DIM, qt * TR, n, stage, wave, lane);
         if (lane < TR)
-            __builtin_amdgcn_global_load_lds((gptr_t)(lse + qslice * n_pad + qt * TR + lane), (lptr_t)lds_lse[t % ATT_STAGES], 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(lse + qslice * n_pad + qt * TR + lane), (lptr_t)stage_lse, 4, 0, 0);
     };
-#pragma unroll
-    for (int t = 0; t < ATT_STAGES - 1; ++t) issue(t);
+    issue(0, lds_a, lse_a);
     u32x4 kf[NB][M::FRAGS];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) load_stationary<T>(Ks, k0 + 32 * kb, n, lane, kf[kb]);
@@ -389,13 +392,11 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) part[kb][0] = part[kb][1] = 0.f;
     int qt = first - 1;
-    for (int s = 0; s < steps; ++s) {
-        const u32x4 *cur = lds[s % ATT_STAGES];
-        const float *cur_lse = lds_lse[s % ATT_STAGES];
+    auto step = [&](int s, const u32x4 *cur, const float *cur_lse, u32x4 *nxt, float *nxt_lse) {
         qt = qt == last ? first : qt + 1;                     // query tile of step s (the heads follow one another)
-        wait_vmcnt<(ATT_STAGES - 2) * (TL::PER_THREAD + 1)>();
+        wait_vmcnt<0>();
         barrier_no_fence();
-        issue(s + ATT_STAGES - 1);
+        issue(s + 1, nxt, nxt_lse);
         if constexpr (NB == 2) {
             if (qt * TR >= k0 + 32 * NB - 1) {
                 // every query of the tile follows every key of this wave: four full blocks
@@ -415,7 +416,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, kf[1]);
                 colsum_update(acc, cur_lse, 1, lane, c, part[1]);
-                continue;
+                return;
             }
         }
 #pragma unroll
@@ -436,6 +437,10 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
                 colsum_update(acc, cur_lse, qb, lane, c, part[kb]);
             }
         }
+    };
+    for (int s = 0; s < steps; s += 2) {
+        step(s, lds_a, lse_a, lds_b, lse_b);
+        if (s + 1 < steps) step(s + 1, lds_b, lse_b, lds_a, lse_a);
     }
     wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
 #pragma unroll
