@@ -92,18 +92,48 @@ template <typename T> struct Tile {
     // Rows [row0, row0+TR) of an (N x 128) matrix -> one LDS stage, asynchronously.  One
     // instruction fills 64 consecutive slots (lane l -> slot base + l), so the swizzle is
     // applied on the source side: the lane that fills slot (row, pos) fetches chunk
-    // pos ^ (row mod CH).  Rows >= n_valid are replaced by row n_valid-1 (finite data whose
-    // scores are masked or weighted by zero later); nothing outside [0, n_valid) is read.
-    static __device__ __forceinline__ void issue(const T *base, int row0, int n_valid, u32x4 *stage, int wave, int lane) {
+    // pos ^ (row mod CH).  The byte offsets of a lane's loads relative to the first row of
+    // the tile do not depend on the tile: they are computed once, and a full tile is then
+    // fetched with a scalar base address and no per-lane arithmetic.
+    struct Offsets { uint32_t v[PER_THREAD]; };
+    static __device__ __forceinline__ Offsets offsets(int wave, int lane) {
+        Offsets o;
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int slot0 = (wave * PER_THREAD + i) * 64;
             const int row = slot0 / CH + lane / CH;
             const int pos = lane % CH;
-            const int src_row = min(row0 + row, n_valid - 1);
-            const char *src = reinterpret_cast<const char *>(base + (size_t)src_row * HEAD_DIM) + ((pos ^ (row & (CH - 1))) * 16);
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + slot0), 16, 0, 0);
+            o.v[i] = (uint32_t)(row * (HEAD_DIM * (int)sizeof(T)) + ((pos ^ (row & (CH - 1))) * 16));
         }
+        return o;
+    }
+    // the same offsets for a ragged tile with only rows_valid (1 <= rows_valid < TR) rows:
+    // rows past the end are replaced by the last valid row (finite data whose scores are
+    // masked or weighted by zero later), so that nothing outside the matrix is read
+    static __device__ __forceinline__ Offsets offsets_clamped(int wave, int lane, int rows_valid) {
+        Offsets o;
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int slot0 = (wave * PER_THREAD + i) * 64;
+            const int row = slot0 / CH + lane / CH;
+            const int pos = lane % CH;
+            o.v[i] = (uint32_t)(min(row, rows_valid - 1) * (HEAD_DIM * (int)sizeof(T)) + ((pos ^ (row & (CH - 1))) * 16));
+        }
+        return o;
+    }
+    // Rows [row0, row0+TR) of the matrix whose row 0 is at `base`, clamped to n_valid rows.  The
+    // tile's first row goes through readfirstlane so that it stays in scalar registers and the
+    // loads take the (scalar base + 32-bit lane offset) form.
+    static __device__ __forceinline__ void issue(const T *base, int row0, int n_valid, const Offsets &full, u32x4 *stage,
+                                                 int wave, int lane) {
+        Offsets o = full;
+        if (row0 + TR > n_valid) o = offsets_clamped(wave, lane, n_valid - row0);
+        const uint64_t u = reinterpret_cast<uint64_t>(base + (size_t)row0 * HEAD_DIM);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+        const char *first_row = reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(first_row + o.v[i]), (lptr_t)(stage + (wave * PER_THREAD + i) * 64), 16, 0, 0);
     }
     // fragment f of 32-row block blk for this lane (MFMA A operand)
     static __device__ __forceinline__ u32x4 frag(const u32x4 *lds, int blk, int f, int lane) {
@@ -157,30 +187,41 @@ __device__ __forceinline__ float max16(const f32x16 &v) {
     return fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), fmaxf(e, v[15]));
 }
 
+constexpr float M_INIT = -3.0e38f;       // "no score seen yet": finite, so that no inf - inf arises
+
 // pass 1: the online (max, sum) of a row absorbs 16 more scores (-inf = masked)
 __device__ __forceinline__ void rowstat_update(const f32x16 &acc, float c, float &m_run, float &l_run) {
     const float m_new = fmaxf(m_run, max16(acc));
-    const float mc = m_new > -INFINITY ? m_new * c : 0.f;     // nothing seen yet: any finite reference works
+    const float mc = m_new * c;
     float p0 = 0.f, p1 = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; i += 2) {
         p0 += __builtin_amdgcn_exp2f(fmaf(acc[i], c, -mc));
         p1 += __builtin_amdgcn_exp2f(fmaf(acc[i + 1], c, -mc));
     }
-    l_run = l_run * __builtin_amdgcn_exp2f(m_run * c - mc) + (p0 + p1);
+    // (the difference is taken before the scaling: M_INIT * c - round(M_INIT * c), fused, would be
+    // the rounding error of a huge product instead of zero)
+    l_run = l_run * __builtin_amdgcn_exp2f((m_run - m_new) * c) + (p0 + p1);
     m_run = m_new;
 }
 
-// pass 2: part[0..1] += exp2(c * acc - L) with L read from the tile's row statistics in LDS
-// (accumulator i of lane l is row 8*(i/4) + 4*(l/32) + i%4 of the 32-row block)
-__device__ __forceinline__ void colsum_update(const f32x16 &acc, const float *lse_tile, int blk, int lane, float c, float *part) {
+// pass 2: the row statistics L of a 32-row block of the streamed tile, in the order of a
+// lane's accumulators (accumulator i of lane l is row 8*(i/4) + 4*(l/32) + i%4)
+struct RowStats { f32x4 v[4]; };
+__device__ __forceinline__ RowStats load_rowstats(const float *lse_tile, int blk, int lane) {
+    RowStats L;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) L.v[r] = *reinterpret_cast<const f32x4 *>(&lse_tile[32 * blk + 8 * r + 4 * (lane >> 5)]);
+    return L;
+}
+// part[0..1] += exp2(c * acc - L)
+__device__ __forceinline__ void colsum_update(const f32x16 &acc, const RowStats &L, float c, float *part) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const f32x4 L = *reinterpret_cast<const f32x4 *>(&lse_tile[32 * blk + 8 * r + 4 * (lane >> 5)]);
-        part[0] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r], c, -L[0]));
-        part[1] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 1], c, -L[1]));
-        part[0] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 2], c, -L[2]));
-        part[1] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 3], c, -L[3]));
+        part[0] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r], c, -L.v[r][0]));
+        part[1] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 1], c, -L.v[r][1]));
+        part[0] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 2], c, -L.v[r][2]));
+        part[1] += __builtin_amdgcn_exp2f(fmaf(acc[4 * r + 3], c, -L.v[r][3]));
     }
 }
 
@@ -226,6 +267,18 @@ __device__ __forceinline__ f32x16 score_block8(const u32x4 *a, const u32x4 *bfra
 // pass 1: row log-sum-exp
 // ------------------------------------------------------------------------------------------
 
+// accumulator i of lane l: is its row index inside the 32x32 block above / below the lane's column?
+__device__ __forceinline__ void mask_rows_above_col(f32x16 &acc, int lane) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (acc_row(i, lane) > (lane & 31)) acc[i] = -INFINITY;
+}
+__device__ __forceinline__ void mask_rows_below_col(f32x16 &acc, int lane) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (acc_row(i, lane) < (lane & 31)) acc[i] = -INFINITY;
+}
+
 template <typename T>
 __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                  float *__restrict__ lse, const int32_t *__restrict__ seq_lens,
@@ -257,9 +310,11 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
 
     const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
     const int steps = q_last / TR + 1;                        // key tiles 0 .. steps-1
-    // tile 0 starts its way into LDS; tile indices past the end are clamped so that every step
-    // issues the same number of loads (the waits below count instructions)
-    TL::issue(Ks, 0, n, lds_a, wave, lane);
+    const typename TL::Offsets off = TL::offsets(wave, lane);
+    auto issue = [&](int t, u32x4 *stage) {                   // key tile t on its way into LDS
+        TL::issue(Ks, t * TR, n, off, stage, wave, lane);
+    };
+    issue(0, lds_a);
 
     u32x4 qf[NB][M::FRAGS];
 #pragma unroll
@@ -267,17 +322,23 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
 
     float m_run[NB], l_run[NB];
 #pragma unroll
-    for (int qb = 0; qb < NB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    for (int qb = 0; qb < NB; ++qb) { m_run[qb] = M_INIT; l_run[qb] = 0.f; }
+
+    // (16-bit types: TR = 64 = the rows of a wave) key tiles before `diag` lie entirely below
+    // this wave's diagonal, tile `diag` holds it, later tiles are in this wave's future; a wave
+    // without valid rows computes nothing
+    const int diag = q0 < n ? q0 / TR : -1;
 
     auto step = [&](int s, const u32x4 *cur, u32x4 *nxt) {
         // this thread's part of tile s has landed; after the barrier everybody's part has, and
         // everybody is done with the stage that tile s+1 now overwrites
         wait_vmcnt<0>();
         barrier_no_fence();
-        TL::issue(Ks, min(s + 1, steps - 1) * TR, n, nxt, wave, lane);
+        if (s + 1 < steps) issue(s + 1, nxt);
         if constexpr (NB == 2) {
-            if (s * TR + TR - 1 <= q0) {
-                // every key of the tile precedes every query of this wave: four full blocks
+            // the fences keep the scheduler from hoisting later blocks' LDS reads, which would
+            // not fit the register budget
+            if (s < diag) {                                   // four full blocks
                 u32x4 a[8];
                 load_frags8<T>(cur, 0, lane, a);
                 f32x16 acc = score_block8<T>(a, qf[0]);
@@ -292,25 +353,40 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, qf[1]);
                 rowstat_update(acc, c, m_run[1], l_run[1]);
-                return;
+            } else if (s == diag) {                           // two blocks on the diagonal, one below it
+                u32x4 a[8];
+                load_frags8<T>(cur, 0, lane, a);              // keys q0 .. q0+31
+                f32x16 acc = score_block8<T>(a, qf[0]);
+                mask_rows_above_col(acc, lane);               // accumulator rows are keys, columns queries
+                rowstat_update(acc, c, m_run[0], l_run[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[1]);
+                load_frags8<T>(cur, 1, lane, a);              // keys q0+32 .. q0+63
+                rowstat_update(acc, c, m_run[1], l_run[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[1]);
+                mask_rows_above_col(acc, lane);
+                rowstat_update(acc, c, m_run[1], l_run[1]);
             }
-        }
+        } else {
+            if (diag < 0) return;
 #pragma unroll
-        for (int kb = 0; kb < NB; ++kb) {
-            const int key0 = s * TR + 32 * kb;
+            for (int kb = 0; kb < NB; ++kb) {
+                const int key0 = s * TR + 32 * kb;
 #pragma unroll
-            for (int qb = 0; qb < NB; ++qb) {
-                const int qrow0 = q0 + 32 * qb;
-                if (key0 > qrow0 + 31) continue;             // every key of the block is in the future
-                f32x16 acc = score_block<T>(cur, kb, qf[qb], lane);
-                // acc[i]: key = key0 + acc_row(i), query = qrow0 + lane%32
-                if (key0 + 31 > qrow0) {
-                    const int q = qrow0 + (lane & 31);
+                for (int qb = 0; qb < NB; ++qb) {
+                    const int qrow0 = q0 + 32 * qb;
+                    if (key0 > qrow0 + 31) continue;         // every key of the block is in the future
+                    f32x16 acc = score_block<T>(cur, kb, qf[qb], lane);
+                    // acc[i]: key = key0 + acc_row(i), query = qrow0 + lane%32
+                    if (key0 + 31 > qrow0) {
+                        const int q = qrow0 + (lane & 31);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (key0 + acc_row(i, lane) > q) acc[i] = -INFINITY;
+                        for (int i = 0; i < 16; ++i)
+                            if (key0 + acc_row(i, lane) > q) acc[i] = -INFINITY;
+                    }
+                    rowstat_update(acc, c, m_run[qb], l_run[qb]);
                 }
-                rowstat_update(acc, c, m_run[qb], l_run[qb]);
             }
         }
     };
@@ -325,9 +401,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     for (int qb = 0; qb < NB; ++qb) {
         const float m_o = __shfl_xor(m_run[qb], 32, WAVE), l_o = __shfl_xor(l_run[qb], 32, WAVE);
         const float m = fmaxf(m_run[qb], m_o);
-        float l = 0.f;
-        if (m_run[qb] > -INFINITY) l += l_run[qb] * __builtin_amdgcn_exp2f((m_run[qb] - m) * c);
-        if (m_o > -INFINITY) l += l_o * __builtin_amdgcn_exp2f((m_o - m) * c);
+        const float l = l_run[qb] * __builtin_amdgcn_exp2f((m_run[qb] - m) * c) + l_o * __builtin_amdgcn_exp2f((m_o - m) * c);
         const int q = q0 + 32 * qb + (lane & 31);
         if (lane < 32 && q < n_pad) lse[(size_t)qslice * n_pad + q] = q < n ? m * c + __log2f(l) : INFINITY;
     }
@@ -347,8 +421,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     using TL = Tile<T>;
     constexpr int NB = M::NBLK, TR = TL::TR;
     constexpr int KEYS_PER_BLOCK = ATT_WAVES * 32 * NB;
-    // one LDS object per stage: the compiler then knows that the fragment reads of a step do
-    // not touch the stage the next tile is being loaded into, and does not wait for that load
+    // one LDS object per stage (see attn_lse_kernel)
     __shared__ u32x4 lds_a[TL::SLOTS], lds_b[TL::SLOTS];
     __shared__ __attribute__((aligned(16))) float lse_a[64], lse_b[64];
 
@@ -368,73 +441,102 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     }
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
 
-    const int first = k_begin / TR;                           // first query tile that sees these keys
+    // Query tiles first .. last see these keys.  They are streamed from the last one down, head
+    // after head: every workgroup of a slice then starts at the same tile and walks down in step
+    // with the others, so that a tile is fetched from memory once for all of them.
+    const int first = k_begin / TR;
     const int last = (n - 1) / TR;
-    const int steps_per_head = last - first + 1;
-    const int steps = steps_per_head * G;
-    // tile t of the sequence (g, qt): Q rows and their statistics -> LDS; every wave issues the
-    // (identical) statistics load so that all waves count the same number of instructions
-    auto issue = [&](int t, u32x4 *stage, float *stage_lse) {
-        t = min(t, steps - 1);
-        const int g = t / steps_per_head, qt = first + t % steps_per_head;
-        const size_t qslice = (size_t)b * H * G + (size_t)h * G + g;
-        TL::issue(Q + qslice * N * HEAD_DIM, qt * TR, n, stage, wave, lane);
+    const int steps = (last - first + 1) * G;
+    const typename TL::Offsets off = TL::offsets(wave, lane);
+    auto issue = [&](int g, int qt, u32x4 *stage, float *stage_lse) {   // Q rows and their statistics -> LDS
+        const size_t qslice = ((size_t)b * H + h) * G + g;
+        const T *Qh = Q + qslice * N * HEAD_DIM;
+        const int row0 = qt * TR;
+        TL::issue(Qh, row0, n, off, stage, wave, lane);
         if (lane < TR)
-            __builtin_amdgcn_global_load_lds((gptr_t)(lse + qslice * n_pad + qt * TR + lane), (lptr_t)stage_lse, 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(lse + qslice * n_pad + row0 + lane), (lptr_t)stage_lse, 4, 0, 0);
     };
-    issue(0, lds_a, lse_a);
+    int g_next = 0, qt_next = last;                           // the tile that is loaded next
+    auto issue_next = [&](u32x4 *stage, float *stage_lse) {
+        issue(g_next, qt_next, stage, stage_lse);
+        if (qt_next == first) { qt_next = last; ++g_next; } else --qt_next;
+    };
+    issue_next(lds_a, lse_a);
     u32x4 kf[NB][M::FRAGS];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) load_stationary<T>(Ks, k0 + 32 * kb, n, lane, kf[kb]);
 
-    float colsum[NB];
     float part[NB][2];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) part[kb][0] = part[kb][1] = 0.f;
-    int qt = first - 1;
+
+    // (16-bit types: TR = 64 = the keys of a wave) query tiles after `diag` lie entirely below
+    // this wave's diagonal, tile `diag` holds it, earlier tiles precede all of the wave's keys;
+    // a wave without valid keys computes nothing
+    const int diag = k0 < n ? k0 / TR : last + 1;
+    int qt = last + 1;                                        // tile of the current step
     auto step = [&](int s, const u32x4 *cur, const float *cur_lse, u32x4 *nxt, float *nxt_lse) {
-        qt = qt == last ? first : qt + 1;                     // query tile of step s (the heads follow one another)
+        qt = qt == first ? last : qt - 1;
         wait_vmcnt<0>();
         barrier_no_fence();
-        issue(s + 1, nxt, nxt_lse);
+        if (s + 1 < steps) issue_next(nxt, nxt_lse);
         if constexpr (NB == 2) {
-            if (qt * TR >= k0 + 32 * NB - 1) {
-                // every query of the tile follows every key of this wave: four full blocks
-                // (the fences keep the scheduler from hoisting later blocks' LDS reads, which
-                // would not fit the register budget)
+            // the fences keep the scheduler from hoisting later blocks' LDS reads, which would
+            // not fit the register budget
+            if (qt > diag) {                                  // four full blocks
                 u32x4 a[8];
                 load_frags8<T>(cur, 0, lane, a);
+                RowStats L = load_rowstats(cur_lse, 0, lane);
                 f32x16 acc = score_block8<T>(a, kf[0]);
-                colsum_update(acc, cur_lse, 0, lane, c, part[0]);
+                colsum_update(acc, L, c, part[0]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, kf[1]);
                 load_frags8<T>(cur, 1, lane, a);              // in flight during the reduction below
-                colsum_update(acc, cur_lse, 0, lane, c, part[1]);
+                colsum_update(acc, L, c, part[1]);
                 __builtin_amdgcn_sched_barrier(0);
+                L = load_rowstats(cur_lse, 1, lane);
                 acc = score_block8<T>(a, kf[0]);
-                colsum_update(acc, cur_lse, 1, lane, c, part[0]);
+                colsum_update(acc, L, c, part[0]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, kf[1]);
-                colsum_update(acc, cur_lse, 1, lane, c, part[1]);
-                return;
+                colsum_update(acc, L, c, part[1]);
+            } else if (qt == diag) {                          // two blocks on the diagonal, one below it
+                u32x4 a[8];
+                load_frags8<T>(cur, 0, lane, a);              // queries k0 .. k0+31
+                RowStats L = load_rowstats(cur_lse, 0, lane);
+                f32x16 acc = score_block8<T>(a, kf[0]);
+                load_frags8<T>(cur, 1, lane, a);              // queries k0+32 .. k0+63
+                mask_rows_below_col(acc, lane);               // accumulator rows are queries, columns keys
+                colsum_update(acc, L, c, part[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                L = load_rowstats(cur_lse, 1, lane);
+                acc = score_block8<T>(a, kf[0]);
+                colsum_update(acc, L, c, part[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, kf[1]);
+                mask_rows_below_col(acc, lane);
+                colsum_update(acc, L, c, part[1]);
             }
-        }
+        } else {
+            if (k0 >= n) return;
 #pragma unroll
-        for (int qb = 0; qb < NB; ++qb) {
-            const int qrow0 = qt * TR + 32 * qb;
+            for (int qb = 0; qb < NB; ++qb) {
+                const int qrow0 = qt * TR + 32 * qb;
+                const RowStats L = load_rowstats(cur_lse, qb, lane);
 #pragma unroll
-            for (int kb = 0; kb < NB; ++kb) {
-                const int key0 = k0 + 32 * kb;
-                if (qrow0 + 31 < key0) continue;             // every query of the block precedes the keys
-                f32x16 acc = score_block<T>(cur, qb, kf[kb], lane);
-                // acc[i]: query = qrow0 + acc_row(i), key = key0 + lane%32
-                if (qrow0 < key0 + 31) {                      // block touches the diagonal
-                    const int key = key0 + (lane & 31);
+                for (int kb = 0; kb < NB; ++kb) {
+                    const int key0 = k0 + 32 * kb;
+                    if (qrow0 + 31 < key0) continue;         // every query of the block precedes the keys
+                    f32x16 acc = score_block<T>(cur, qb, kf[kb], lane);
+                    // acc[i]: query = qrow0 + acc_row(i), key = key0 + lane%32
+                    if (qrow0 < key0 + 31) {                  // block touches the diagonal
+                        const int key = key0 + (lane & 31);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (qrow0 + acc_row(i, lane) < key) acc[i] = -INFINITY;
+                        for (int i = 0; i < 16; ++i)
+                            if (qrow0 + acc_row(i, lane) < key) acc[i] = -INFINITY;
+                    }
+                    colsum_update(acc, L, c, part[kb]);
                 }
-                colsum_update(acc, cur_lse, qb, lane, c, part[kb]);
             }
         }
     };
@@ -444,10 +546,9 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     }
     wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
 #pragma unroll
-    for (int kb = 0; kb < NB; ++kb) colsum[kb] = part[kb][0] + part[kb][1];
-#pragma unroll
     for (int kb = 0; kb < NB; ++kb) {
-        const float total = colsum[kb] + __shfl_xor(colsum[kb], 32, WAVE);
+        const float colsum = part[kb][0] + part[kb][1];
+        const float total = colsum + __shfl_xor(colsum, 32, WAVE);
         const int key = k0 + 32 * kb + (lane & 31);
         if (lane < 32 && key < N) mass_s[key] = key < n ? total : 0.f;
     }
