@@ -17,68 +17,96 @@ namespace kvm {
 // ------------------------------------------------------------------------------------------
 
 constexpr int COS_BLOCK = 256;
+constexpr int COS_GROUPS = COS_BLOCK / 16;                  // 16-lane groups per workgroup
 constexpr int COS_ROWS_PER_GROUP = 16;                      // consecutive rows per 16-lane group
-constexpr int COS_ROWS_PER_BLOCK = (COS_BLOCK / 16) * COS_ROWS_PER_GROUP;
-constexpr int COS_BATCH = 8;                                 // rows in flight per group
+constexpr int COS_ROWS_PER_BLOCK = COS_GROUPS * COS_ROWS_PER_GROUP;
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// partial dot product of a lane's 8 elements of two rows, fp32 accumulation (products of two
+// 16-bit values are exact in fp32)
+template <typename T> struct RowDot;
+template <> struct RowDot<half_t> {
+    static __device__ __forceinline__ float dot(const Elem<half_t>::Raw &a, const Elem<half_t>::Raw &b) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t ai = a.v[i], bi = b.v[i];
+            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ai), __builtin_bit_cast(f16x2, bi), s, false);
+        }
+        return s;
+    }
+};
+template <> struct RowDot<bf16_t> {
+    static __device__ __forceinline__ float dot(const Elem<bf16_t>::Raw &a, const Elem<bf16_t>::Raw &b) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t ai = a.v[i], bi = b.v[i];
+            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ai), __builtin_bit_cast(bf16x2, bi), s, false);
+        }
+        return s;
+    }
+};
+template <> struct RowDot<float> {
+    static __device__ __forceinline__ float dot(const Elem<float>::Raw &a, const Elem<float>::Raw &b) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { s0 = fmaf(a.a[i], b.a[i], s0); s1 = fmaf(a.b[i], b.b[i], s1); }
+        return s0 + s1;
+    }
+};
+
+// 1/sqrt(x) for a squared norm; 0 when the squared norm is zero or below the normal fp32 range
+// (such a key counts as a zero-norm key: its similarities are 0)
+__device__ __forceinline__ float inv_norm(float nn) { return nn >= 1.17549435e-38f ? __builtin_amdgcn_rsqf(nn) : 0.f; }
 
 template <typename T>
 __global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restrict__ K, float *__restrict__ sim,
                                                                  const int32_t *__restrict__ seq_lens, int H, int N,
                                                                  int tiles_per_slice)
 {
+    typedef typename Elem<T>::Raw Raw;
+    __shared__ Raw last_row[COS_GROUPS][16];                // the last row of every group, for its successor
+
     const int slice = blockIdx.x / tiles_per_slice;
     const int tile = blockIdx.x - slice * tiles_per_slice;
     const int n = clamp_len(seq_lens, slice / H, N);
-    const int c = threadIdx.x & 15;
-    const int j0 = tile * COS_ROWS_PER_BLOCK + (threadIdx.x >> 4) * COS_ROWS_PER_GROUP;
-    if (j0 >= N) return;
-    const T *Ks = K + (size_t)slice * N * HEAD_DIM;
+    const int c = threadIdx.x & 15, group = threadIdx.x >> 4;
+    const int j_block = tile * COS_ROWS_PER_BLOCK;
+    const int j0 = j_block + group * COS_ROWS_PER_GROUP;
     float *sims = sim + (size_t)slice * N;
-
-    float prev[8];
-    float nprev = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) prev[i] = 0.f;
-    if (j0 >= 1 && j0 - 1 < n) {
-        Elem<T>::to_float(Elem<T>::load(Ks + (size_t)(j0 - 1) * HEAD_DIM, c), prev);
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s = fmaf(prev[i], prev[i], s);
-        nprev = row16_sum(s);
+    if (j_block >= n) {                                      // padding only: defined zeros, nothing read
+        if (c == 0)
+            for (int i = 0; i < COS_ROWS_PER_GROUP; ++i)
+                if (j0 + i < N) sims[j0 + i] = 0.f;
+        return;
     }
+    const T *Ks = K + (size_t)slice * N * HEAD_DIM;
+
+    // every row of the group at once (rows past the end are replaced by the last valid one and
+    // never used), plus the row before the workgroup's first for group 0
+    Raw raw[COS_ROWS_PER_GROUP];
 #pragma unroll
-    for (int base = 0; base < COS_ROWS_PER_GROUP; base += COS_BATCH) {
-        typename Elem<T>::Raw raw[COS_BATCH];
+    for (int i = 0; i < COS_ROWS_PER_GROUP; ++i) raw[i] = Elem<T>::load(Ks + (size_t)min(j0 + i, n - 1) * HEAD_DIM, c);
+    Raw prev = raw[0];
+    if (group == 0 && j0 >= 1) prev = Elem<T>::load(Ks + (size_t)(j0 - 1) * HEAD_DIM, c);
+    last_row[group][c] = raw[COS_ROWS_PER_GROUP - 1];
+    __syncthreads();
+    if (group > 0) prev = last_row[group - 1][c];
+
+    float r_prev = inv_norm(row16_sum(RowDot<T>::dot(prev, prev)));
 #pragma unroll
-        for (int i = 0; i < COS_BATCH; ++i) {
-            const int j = j0 + base + i;
-            if (j < n) raw[i] = Elem<T>::load(Ks + (size_t)j * HEAD_DIM, c);
-        }
-#pragma unroll
-        for (int i = 0; i < COS_BATCH; ++i) {
-            const int j = j0 + base + i;
-            if (j >= N) break;
-            if (j >= n) {                                    // padding: defined, never read as data
-                if (c == 0) sims[j] = 0.f;
-                continue;
-            }
-            float cur[8];
-            Elem<T>::to_float(raw[i], cur);
-            float dot = 0.f, nn = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                dot = fmaf(cur[e], prev[e], dot);
-                nn = fmaf(cur[e], cur[e], nn);
-            }
-            dot = row16_sum(dot);
-            nn = row16_sum(nn);
-            float s = 0.f;                                   // zero norm or first token: similarity 0
-            if (j > 0 && nn > 0.f && nprev > 0.f) s = dot / (sqrtf(nn) * sqrtf(nprev));
-            if (c == 0) sims[j] = s;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) prev[e] = cur[e];
-            nprev = nn;
-        }
+    for (int i = 0; i < COS_ROWS_PER_GROUP; ++i) {
+        const int j = j0 + i;
+        const float dot = row16_sum(RowDot<T>::dot(raw[i], prev));
+        const float r = inv_norm(row16_sum(RowDot<T>::dot(raw[i], raw[i])));
+        // zero norm, first token of the sequence or padding: similarity 0
+        const float s = (j > 0 && j < n) ? (dot * r) * r_prev : 0.f;
+        if (c == (i & 15) && j < N) sims[j] = s;
+        prev = raw[i];
+        r_prev = r;
     }
 }
 

@@ -166,6 +166,25 @@ def test_identify_special_keys():
     assert g["sim"][0, 2, 105] == 0 and g["sim"][0, 2, 106] == 0
 
 
+@pytest.mark.parametrize("dtype,scale", [("f16", 2.0 ** -20), ("f16", 200.0), ("bf16", 1e-15), ("bf16", 1e15), ("f32", 1e-15)])
+def test_identify_key_magnitudes(dtype, scale):
+    """Keys in the subnormal range of the storage type, and very small and very large keys: the
+    similarity does not depend on the scale of the keys."""
+    n = 500
+    _say(f"identify: keys scaled by {scale} ({dtype})")
+    rng = np.random.default_rng(5)
+    x = np.zeros((1, 2, n, 128), np.float32)
+    x[0, :, 0] = rng.standard_normal((2, 128))
+    for t in range(1, n):                                    # AR(1) keys, similarity around the threshold
+        x[0, :, t] = 0.75 * x[0, :, t - 1] + np.sqrt(1 - 0.75 ** 2) * rng.standard_normal((2, 128))
+    K = synth.to_storage((x * scale).astype(np.float32), dtype)
+    mass = rng.uniform(1, 2, (1, 2, n))
+    params = kb.kvm_params_for_budget(0.5)
+    g, o = _identify_both(K, mass, dtype, params)
+    np.testing.assert_allclose(g["sim"], o["sim"], atol=2e-6)
+    gu.compare_maps(g, o, None, n, params.threshold, f"{dtype} scale {scale}")
+
+
 def test_identify_ties_in_mass():
     n = 2000
     _say("identify: heavy ties in the scores (top-k and pivot tie-breaks)")
