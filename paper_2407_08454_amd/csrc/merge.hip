@@ -8,8 +8,8 @@
 // (8 elements = 16 B each for 16-bit types), so one wave instruction moves four rows.  Per
 // set: one sweep over its keys for the distances to the pivot (sigma), a second sweep (served
 // by L2, the set was just read) that forms the weights and accumulates keys and values in
-// fp32, then one rounded row is written per output.  Loads are issued 32 rows at a time; a
-// set of up to 32 tokens is read exactly once and held in registers.  Runs of singleton sets
+// fp32, then one rounded row is written per output.  Loads are issued 16 rows at a time; a
+// set of up to 16 tokens is read exactly once and held in registers.  Runs of singleton sets
 // are copied bit for bit.  HBM traffic: K once, V once, 2 M rows out.
 #include "kvm_common.h"
 
@@ -18,9 +18,10 @@ namespace kvm {
 constexpr int MERGE_BLOCK = 64;          // one wave per workgroup: waves finish independently
 constexpr int MERGE_TILE = 64;           // tokens per wave (its sets are those that start in the tile)
 constexpr int PLAN_BLOCK = 256;
-// 4-row groups whose loads are issued together: 32 rows (8 KB of K and 8 KB of V) for the
-// 16-bit types, 16 rows for fp32 (same bytes)
-template <typename T> struct MergeUnroll { static constexpr int value = sizeof(T) == 2 ? 8 : 4; };
+// 4-row groups whose loads are issued together: 16 rows of K and of V.  Larger batches read
+// more sets in a single sweep but cost registers; the kernel is bound by memory latency, and
+// four waves per SIMD with 16-row batches beat two waves with 32-row batches.
+template <typename T> struct MergeUnroll { static constexpr int value = 4; };
 
 struct MergeArgs {
     const int32_t *set_start, *pivot, *n_sets, *seq_lens;
