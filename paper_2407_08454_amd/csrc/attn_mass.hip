@@ -283,7 +283,7 @@ template <typename T>
 __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                  float *__restrict__ lse, const int32_t *__restrict__ seq_lens,
                                                                  int n_qslices, int HG, int G, int N, int n_pad,
-                                                                 int tiles_per_slice, float c)
+                                                                 int tiles_per_slice, int wgs_per_slice, float c)
 {
     using M = Mma<T>;
     using TL = Tile<T>;
@@ -293,24 +293,31 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     // not touch the stage the next tile is being loaded into, and does not wait for that load
     __shared__ u32x4 lds_a[TL::SLOTS], lds_b[TL::SLOTS];
 
-    const TileMap tm = map_block(n_qslices, tiles_per_slice);
+    const TileMap tm = map_block(n_qslices, wgs_per_slice);
     if (!tm.valid) return;
     const int qslice = tm.slice;                              // (b, h*G + g)
-    const int tile = tiles_per_slice - 1 - tm.tile;          // longest rows first
     const int b = qslice / HG;
     const int kvslice = b * (HG / G) + (qslice % HG) / G;
     const int n = clamp_len(seq_lens, b, N);
-    const int q_begin = tile * ROWS_PER_BLOCK;
-    if (q_begin >= n) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar: per-wave branches stay scalar
     const T *Qs = Q + (size_t)qslice * N * HEAD_DIM;
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
+    const typename TL::Offsets off = TL::offsets(wave, lane);
+
+    // Workgroup t of a slice takes row tile tiles-1-t, the one with the longest rows left; with
+    // fewer workgroups than tiles it then also takes tile t, the shortest left, so that all
+    // workgroups of a launch carry the same load.
+    const bool paired = wgs_per_slice < tiles_per_slice;
+    for (int pass = 0; pass < 2; ++pass) {
+    const int tile = pass == 0 ? tiles_per_slice - 1 - tm.tile : tm.tile;
+    if (pass == 1 && (!paired || tm.tile >= tiles_per_slice - 1 - tm.tile)) break;
+    const int q_begin = tile * ROWS_PER_BLOCK;
+    if (q_begin >= n) continue;
     const int q0 = q_begin + wave * 32 * NB;                  // first query row of this wave
 
     const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
     const int steps = q_last / TR + 1;                        // key tiles 0 .. steps-1
-    const typename TL::Offsets off = TL::offsets(wave, lane);
     auto issue = [&](int t, u32x4 *stage) {                   // key tile t on its way into LDS
         TL::issue(Ks, t * TR, n, off, stage, wave, lane);
     };
@@ -404,6 +411,8 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
         const float l = l_run[qb] * __builtin_amdgcn_exp2f((m_run[qb] - m) * c) + l_o * __builtin_amdgcn_exp2f((m_o - m) * c);
         const int q = q0 + 32 * qb + (lane & 31);
         if (lane < 32 && q < n_pad) lse[(size_t)qslice * n_pad + q] = q < n ? m * c + __log2f(l) : INFINITY;
+    }
+    barrier_no_fence();                                       // everybody is done with LDS before the next tile's loads
     }
 }
 
@@ -569,10 +578,14 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
     const int n_q = sh.B * sh.H_kv * sh.G, n_kv = sh.B * sh.H_kv;
     const int n_pad = attn_lse_stride(sh.N);
     {
-        const long long blocks = (long long)((n_q + 7) / 8) * 8 * tiles;
+        // long sequences: half as many workgroups, each with one long and one short row tile
+        // (measured faster from 8 tiles per slice on; below that the second tile's start-up,
+        // which nothing overlaps, costs more than the even load gains)
+        const int wgs = tiles >= 8 ? (tiles + 1) / 2 : tiles;
+        const long long blocks = (long long)((n_q + 7) / 8) * 8 * wgs;
         ProfScope prof("attn_lse_kernel", st);
         hipLaunchKernelGGL(attn_lse_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q, (const T *)K,
-                           lse, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, c);
+                           lse, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c);
         kvm_status rc = check_launch("attn_lse_kernel");
         if (rc != KVM_OK) return rc;
     }
