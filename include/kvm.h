@@ -128,7 +128,8 @@ kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, f
  * Per slice, with n = n_b:
  *   1. conserved tokens: the last floor(recent_ratio n), plus the
  *      floor(heavy_ratio n) largest `mass` among the others (ties: lower index);
- *   2. sim[j] = cosine similarity of k_{j-1} and k_j (Eq. (2)), 0 if a norm is 0;
+ *   2. sim[j] = cosine similarity of k_{j-1} and k_j (Eq. (2)), 0 if a norm is 0
+ *      (norms are accumulated in fp32: a squared norm below 2^-126 counts as 0);
  *   3. token j-1 and j share a set iff sim[j] > threshold and neither is
  *      conserved (Algorithm 1 read as a chain of adjacent tokens); sets are
  *      therefore contiguous, disjoint and cover [0, n); conserved tokens are
