@@ -45,6 +45,11 @@ def main() -> int:
     ap.add_argument("--budget", type=float, default=0.5)
     ap.add_argument("--cpu-slices", type=int, default=512, help="slices the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
+    ap.add_argument("--weights", choices=["gaussian", "average"], default="gaussian",
+                    help="merge weights (average = the average weighted merging of Section 4.2)")
+    ap.add_argument("--pivot", choices=["max-score", "last", "random"], default="max-score",
+                    help="pivot rule (last = largest index, Section 4.2; random = Section 5.4)")
+    ap.add_argument("--sigma", type=float, default=None, help="fixed sigma (Section 5.4) instead of the per-set one")
     ap.add_argument("--gen-workers", type=int, default=None,
                     help="processes that generate the inputs (1 = in this process, e.g. under a profiler)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -80,6 +85,12 @@ def main() -> int:
     Qd, Kd, Vd = dev(Q), dev(K), dev(V)
     sl = None if lens is None else torch.from_numpy(lens).cuda()
     params = kb.kvm_params_for_budget(args.budget)
+    params.weights = {"gaussian": kb.KVM_WEIGHTS_GAUSSIAN, "average": kb.KVM_WEIGHTS_AVERAGE}[args.weights]
+    params.pivot_rule = {"max-score": kb.KVM_PIVOT_MAX_SCORE, "last": kb.KVM_PIVOT_LAST,
+                         "random": kb.KVM_PIVOT_RANDOM}[args.pivot]
+    if args.sigma is not None:
+        params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, args.sigma
+    variant = f"weights {args.weights}, pivot {args.pivot}, sigma {'per set' if args.sigma is None else args.sigma}"
     shape = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(shape, params, "cuda", tdt)
 
@@ -127,7 +138,8 @@ def main() -> int:
     bytes_merge = float(2 * token_slices * d * esz + 2 * M_total * d * esz + 8 * M_total)
     roofline = None
     hbm = {}
-    headline = args.config == 2 and args.layers is None and args.budget == 0.5
+    headline = (args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
+                and args.pivot == "max-score" and args.sigma is None)
 
     def traffic(name):
         return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None
@@ -164,8 +176,10 @@ def main() -> int:
         t0 = time.perf_counter()
         m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
         o = ref.identify_sets(Ks, m.astype(np.float32).astype(np.float64), dtype, params.budget, params.recent_ratio,
-                              params.heavy_ratio, params.threshold, True, buf.cap, ls)
-        ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], seq_lens=ls)
+                              params.heavy_ratio, params.threshold, True, buf.cap, ls, pivot_rule=params.pivot_rule,
+                              pivot_seed=params.pivot_seed)
+        ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
+                  bool(params.value_scale_by_set_size), seq_lens=ls, weights=params.weights)
         cpu_s = time.perf_counter() - t0
         toks = int(N * S if ls is None else ls.sum())
         cores = ref.num_threads()
@@ -178,7 +192,7 @@ def main() -> int:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg['name']}: {B // cfg['batch']} layers x {H} KV heads, "
-                               f"G={G}, N={N}, d={d}, {dtype}, budget {args.budget}, AR(1) keys seed {cfg['seed']}",
+                               f"G={G}, N={N}, d={d}, {dtype}, budget {args.budget}, AR(1) keys seed {cfg['seed']}; {variant}",
                    "slices": B * H, "token_slices_per_step": token_slices, "merged_rows_per_step": M_total,
                    "mean_M_over_n": M_total / token_slices, "slices_with_fallback": int((status != 0).sum())},
         "roofline": roofline, "cpu_baseline": cpu,

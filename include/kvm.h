@@ -60,6 +60,20 @@ typedef enum {
     KVM_SIGMA_FIXED = 1       /* sigma given by the caller (the fixed-sigma study, Sec. 5.4) */
 } kvm_sigma_mode;
 
+/* How the members of a set are weighted (Section 4.2). */
+typedef enum {
+    KVM_WEIGHTS_GAUSSIAN = 0, /* Gaussian kernel around the pivot, Eq. (5), (6)               */
+    KVM_WEIGHTS_AVERAGE = 1   /* every member 1/|S|: the average weighted merging Section 4.2
+                                 starts from                                                   */
+} kvm_weights;
+
+/* Which member of a set is its pivot. */
+typedef enum {
+    KVM_PIVOT_MAX_SCORE = 0,  /* largest aggregated attention score, Eq. (7)                  */
+    KVM_PIVOT_LAST = 1,       /* largest index (Section 4.2, the average-weighted experiment) */
+    KVM_PIVOT_RANDOM = 2      /* drawn at random (Section 5.4, "Choice of Pivotal State")     */
+} kvm_pivot_rule;
+
 typedef struct {
     int32_t B;                /* batch (x layers): every (b, h) slice is independent         */
     int32_t H_kv;             /* KV heads                                                     */
@@ -79,6 +93,9 @@ typedef struct {
     float sigma;              /* used when sigma_mode == KVM_SIGMA_FIXED (must be > 0)        */
     int32_t value_scale_by_set_size; /* 1: value weights are |S| w_i (Sec. 4.2); 0: w_i      */
     int32_t enforce_budget;   /* 1: remove boundaries until M <= floor(beta n_b) (see below)  */
+    int32_t weights;          /* kvm_weights                                                  */
+    int32_t pivot_rule;       /* kvm_pivot_rule                                               */
+    uint64_t pivot_seed;      /* seed of the draws of KVM_PIVOT_RANDOM                        */
 } kvm_params;
 
 /*
@@ -87,7 +104,8 @@ typedef struct {
  * 0.75 for both (the proportions are read as fractions of the length).  Other
  * budgets in (0,1] get recent = 0.34 beta, heavy = 0.24 beta (the 0.50 row
  * scaled).  Sets sigma_mode = MEAN_DIST, value_scale_by_set_size = 1,
- * enforce_budget = 1.  Host call.  KVM_ERR_INVALID_ARG if out == NULL or budget
+ * enforce_budget = 1, weights = GAUSSIAN, pivot_rule = MAX_SCORE, pivot_seed = 0.
+ * Host call.  KVM_ERR_INVALID_ARG if out == NULL or budget
  * is not in (0,1].
  */
 kvm_status kvm_params_for_budget(double budget, kvm_params *out);
@@ -139,7 +157,11 @@ kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, f
  *      largest sim are removed (ties: higher index first), i.e. the slice's
  *      threshold is lowered just enough; if there are not enough of them all are
  *      removed and KVM_SLICE_INFEASIBLE is set;
- *   5. pivot of a set = its token with the largest mass (ties: lowest index).
+ *   5. pivot of a set = its token with the largest mass (ties: lowest index);
+ *      KVM_PIVOT_LAST: its last token; KVM_PIVOT_RANDOM: first token + floor(u m / 2^32)
+ *      for a set of m tokens, u = upper 32 bits of the SplitMix64 output function at the
+ *      counter pivot_seed + (slice index b*H_kv+h) * 2^32 + first token (mod 2^64), so the
+ *      draws can be reproduced anywhere.
  *   K            in   (B, H_kv, N, d)
  *   mass         in   (B, H_kv, N) float32 (finite; as written by kvm_attn_mass)
  *   set_id       out  (B, H_kv, N) int32: set of token j, -1 at positions >= n
@@ -164,6 +186,8 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
  *     K_out[s] = sum w_j k_j,   V_out[s] = c sum w_j v_j,  c = |S| or 1.
  * sigma: KVM_SIGMA_MEAN_DIST -> sum_j D_j / (sqrt(2) |S|) (all g = 1 when it is
  * 0, so a singleton is copied bit for bit); KVM_SIGMA_FIXED -> params->sigma.
+ * With weights == KVM_WEIGHTS_AVERAGE every g_j is 1 (w_j = 1/|S|; pivot and sigma
+ * are not used).
  *   K, V        in   (B, H_kv, N, d)
  *   set_start, pivot, n_sets  in   as written by kvm_identify_sets (entries are
  *               clamped to the slice, so inconsistent maps cannot cause

@@ -39,6 +39,14 @@
  *   R-c3  sigma == 0 (all keys of the set equal the pivot) gives g = 1.
  *   R-c4  value weights are the key weights times |S| (Section 4.2), optional.
  *
+ * Variants the paper studies (Section 4.2 first experiment, Section 5.4), selectable here:
+ *   - average weighted merging: every member of a set gets weight 1/|S|
+ *   - pivot = the set's token with the largest index (the choice Section 4.2 makes
+ *     for the average-weighted experiment), or a token drawn at random
+ *     (Section 5.4, "Choice of Pivotal State").  The random draw is a counter-based
+ *     generator (SplitMix64 output function of seed + slice*2^32 + first token of
+ *     the set), so that any implementation draws the same pivots.
+ *
  * Parity pins live in tests/ (closed forms, brute force, invariants).
  */
 #include <math.h>
@@ -52,6 +60,8 @@
 enum { REF_F32 = 0, REF_F16 = 1, REF_BF16 = 2 };
 enum { REF_SLICE_OK = 0, REF_SLICE_FALLBACK = 1, REF_SLICE_INFEASIBLE = 2, REF_SLICE_TRUNCATED = 4 };
 enum { REF_SIGMA_MEAN_DIST = 0, REF_SIGMA_FIXED = 1 };
+enum { REF_WEIGHTS_GAUSSIAN = 0, REF_WEIGHTS_AVERAGE = 1 };
+enum { REF_PIVOT_MAX_SCORE = 0, REF_PIVOT_LAST = 1, REF_PIVOT_RANDOM = 2 };
 
 /* ---- exact widening of storage types ------------------------------------ */
 
@@ -176,6 +186,23 @@ static double cosine(const double *x, const double *y, int d)
     return xy / (sqrt(xx) * sqrt(yy));
 }
 
+/* Output function of SplitMix64 (Steele, Lea, Flood 2014) applied to the counter z. */
+static uint64_t splitmix64_at(uint64_t z)
+{
+    z += 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* Random member of a set of m tokens that starts at token lo of slice bh: the upper 32
+ * bits of the draw scaled to [0, m). */
+static int random_offset(uint64_t seed, int bh, int lo, int m)
+{
+    uint64_t r = splitmix64_at(seed + (((uint64_t)(uint32_t)bh << 32) | (uint32_t)lo));
+    return (int)(((r >> 32) * (uint64_t)m) >> 32);
+}
+
 typedef struct { double v; int idx; } ranked;
 
 static int by_value_desc_index_asc(const void *pa, const void *pb)
@@ -228,13 +255,15 @@ static int walk_sets(int n, const unsigned char *joins, int *first)
  */
 int kvm_ref_identify_sets(int B, int H, int N, int d, int dtype, const int32_t *seq_lens,
                           double budget, double recent_ratio, double heavy_ratio, double threshold,
-                          int enforce_budget, int cap_rows, const void *K, const double *mass,
+                          int enforce_budget, int pivot_rule, uint64_t pivot_seed, int cap_rows, const void *K,
+                          const double *mass,
                           int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets,
                           int32_t *slice_status, double *sim_out, unsigned char *protected_out,
                           double *min_removed_sim)
 {
     int bh;
     if (B < 0 || H < 1 || N < 0 || d < 1 || cap_rows < 0) return 1;
+    if (pivot_rule < REF_PIVOT_MAX_SCORE || pivot_rule > REF_PIVOT_RANDOM) return 1;
     if (!set_id || !set_start || !pivot || !n_sets || !slice_status) return 1;
     if (B && N && (!K || !mass)) return 1;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -292,7 +321,8 @@ int kvm_ref_identify_sets(int B, int H, int N, int d, int dtype, const int32_t *
             M = walk_sets(n, joins, first);
         }
 
-        /* number the sets in sequence order; pivot = argmax of the score, first on ties */
+        /* number the sets in sequence order; pivot = argmax of the score, first on ties
+         * (Eq. (7)), or the variant asked for */
         for (j = 0; j < N; ++j) sid[j] = -1;
         for (s = 0; s <= cap_rows; ++s) sst[s] = n;
         for (s = 0; s < cap_rows; ++s) piv[s] = -1;
@@ -304,6 +334,8 @@ int kvm_ref_identify_sets(int B, int H, int N, int d, int dtype, const int32_t *
                 sid[j] = s;
                 if (a[j] > a[p]) p = j;
             }
+            if (pivot_rule == REF_PIVOT_LAST) p = hi - 1;
+            if (pivot_rule == REF_PIVOT_RANDOM) p = lo + random_offset(pivot_seed, bh, lo, hi - lo);
             if (s <= cap_rows) sst[s] = lo;
             if (s < cap_rows) piv[s] = p;
         }
@@ -328,10 +360,15 @@ int kvm_ref_identify_sets(int B, int H, int N, int d, int dtype, const int32_t *
 
 /* Algorithm 2 for one set: keys k[0..m) (rows of d), pivot index p inside the set.
  * Writes the m weights w (they sum to 1). */
-static void set_weights(const double *k, int m, int d, int p, int sigma_mode, double sigma_fixed, double *w)
+static void set_weights(const double *k, int m, int d, int p, int weights_mode, int sigma_mode, double sigma_fixed,
+                        double *w)
 {
     double dist_sum = 0.0, g_sum = 0.0, sigma;
     int j, c;
+    if (weights_mode == REF_WEIGHTS_AVERAGE) { /* average weighted merging, Section 4.2 */
+        for (j = 0; j < m; ++j) w[j] = 1.0 / (double)m;
+        return;
+    }
     for (j = 0; j < m; ++j) { /* w[j] holds ||k_p - k_j|| for now */
         double sq = 0.0;
         for (c = 0; c < d; ++c) {
@@ -358,7 +395,7 @@ static void set_weights(const double *k, int m, int d, int p, int sigma_mode, do
  * tokens of truncated sets).
  */
 int kvm_ref_merge(int B, int H, int N, int d, int dtype, const int32_t *seq_lens, int cap_rows,
-                  int sigma_mode, double sigma_fixed, int value_scale_by_set_size,
+                  int weights_mode, int sigma_mode, double sigma_fixed, int value_scale_by_set_size,
                   const void *K, const void *V, const int32_t *set_start, const int32_t *pivot,
                   const int32_t *n_sets, double *K_out, double *V_out, double *w_out)
 {
@@ -384,7 +421,7 @@ int kvm_ref_merge(int B, int H, int N, int d, int dtype, const int32_t *seq_lens
             double *ko = K_out + ((size_t)bh * cap_rows + s) * d;
             double *vo = V_out + ((size_t)bh * cap_rows + s) * d;
             double vscale = value_scale_by_set_size ? (double)m : 1.0; /* [reading] R-c4 */
-            set_weights(kd + (size_t)lo * d, m, d, piv[s] - lo, sigma_mode, sigma_fixed, w);
+            set_weights(kd + (size_t)lo * d, m, d, piv[s] - lo, weights_mode, sigma_mode, sigma_fixed, w);
             for (c = 0; c < d; ++c) { ko[c] = 0.0; vo[c] = 0.0; }
             for (j = 0; j < m; ++j) /* Def. 4.2, Eq. (4) */
                 for (c = 0; c < d; ++c) {
@@ -407,6 +444,10 @@ int kvm_ref_num_threads(void)
     return 1;
 #endif
 }
+
+/* The pivot generator, exported for the tests (published test vectors). */
+uint64_t kvm_ref_splitmix64_at(uint64_t z) { return splitmix64_at(z); }
+int kvm_ref_random_offset(uint64_t seed, int bh, int lo, int m) { return random_offset(seed, bh, lo, m); }
 
 /* Widening helpers exported for the tests (exactness of the fp16 / bf16 readers). */
 double kvm_ref_half_to_double(uint16_t h) { return half_to_double(h); }

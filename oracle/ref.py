@@ -20,6 +20,8 @@ _LIB = os.path.join(_HERE, "libkvm_ref.so")
 _DTYPE = {"f32": 0, "f16": 1, "bf16": 2}
 SLICE_OK, SLICE_FALLBACK, SLICE_INFEASIBLE, SLICE_TRUNCATED = 0, 1, 2, 4
 SIGMA_MEAN_DIST, SIGMA_FIXED = 0, 1
+WEIGHTS_GAUSSIAN, WEIGHTS_AVERAGE = 0, 1
+PIVOT_MAX_SCORE, PIVOT_LAST, PIVOT_RANDOM = 0, 1, 2
 
 _lib = None
 
@@ -41,6 +43,10 @@ def _load():
         _lib.kvm_ref_half_to_double.argtypes = [ctypes.c_uint16]
         _lib.kvm_ref_bf16_to_double.restype = ctypes.c_double
         _lib.kvm_ref_bf16_to_double.argtypes = [ctypes.c_uint16]
+        _lib.kvm_ref_splitmix64_at.restype = ctypes.c_uint64
+        _lib.kvm_ref_splitmix64_at.argtypes = [ctypes.c_uint64]
+        _lib.kvm_ref_random_offset.restype = ctypes.c_int
+        _lib.kvm_ref_random_offset.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     return _lib
 
 
@@ -70,6 +76,14 @@ def bf16_to_double(bits: int) -> float:
     return _load().kvm_ref_bf16_to_double(bits)
 
 
+def splitmix64_at(z: int) -> int:
+    return int(_load().kvm_ref_splitmix64_at(z & 0xFFFFFFFFFFFFFFFF))
+
+
+def random_offset(seed: int, slice_index: int, first_token: int, m: int) -> int:
+    return int(_load().kvm_ref_random_offset(seed & 0xFFFFFFFFFFFFFFFF, slice_index, first_token, m))
+
+
 def num_threads() -> int:
     return int(_load().kvm_ref_num_threads())
 
@@ -92,7 +106,7 @@ def attn_mass(Q, K, dtype: str, G: int = 1, seq_lens=None):
 
 def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy_ratio: float,
                   threshold: float, enforce_budget: bool = True, cap_rows: int | None = None,
-                  seq_lens=None):
+                  seq_lens=None, pivot_rule: int = PIVOT_MAX_SCORE, pivot_seed: int = 0):
     """K (B, H, N, d), mass (B, H, N) -> dict of index maps (see kvm_ref.c)."""
     lib = _load()
     _check_storage(K, dtype)
@@ -114,9 +128,10 @@ def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy
         cap_rows=cap_rows,
     )
     lib.kvm_ref_identify_sets.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] + [ctypes.c_double] * 4 + \
-        [ctypes.c_int] * 2 + [ctypes.c_void_p] * 10
+        [ctypes.c_int] * 2 + [ctypes.c_uint64, ctypes.c_int] + [ctypes.c_void_p] * 10
     rc = lib.kvm_ref_identify_sets(B, H, N, d, _DTYPE[dtype], _ptr(sl), float(budget), float(recent_ratio),
-                                   float(heavy_ratio), float(threshold), int(bool(enforce_budget)), cap_rows,
+                                   float(heavy_ratio), float(threshold), int(bool(enforce_budget)), int(pivot_rule),
+                                   int(pivot_seed), cap_rows,
                                    _ptr(K), _ptr(mass), _ptr(out["set_id"]), _ptr(out["set_start"]),
                                    _ptr(out["pivot"]), _ptr(out["n_sets"]), _ptr(out["status"]),
                                    _ptr(out["sim"]), _ptr(out["protected"]), _ptr(out["min_removed_sim"]))
@@ -126,7 +141,8 @@ def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy
 
 
 def merge(K, V, dtype: str, set_start, pivot, n_sets, sigma_mode: int = SIGMA_MEAN_DIST,
-          sigma: float = 0.0, value_scale_by_set_size: bool = True, seq_lens=None):
+          sigma: float = 0.0, value_scale_by_set_size: bool = True, seq_lens=None,
+          weights: int = WEIGHTS_GAUSSIAN):
     """-> (K_out, V_out (B, H, cap_rows, d) fp64 with rows >= n_sets zero, w (B, H, N))."""
     lib = _load()
     _check_storage(K, dtype)
@@ -141,9 +157,9 @@ def merge(K, V, dtype: str, set_start, pivot, n_sets, sigma_mode: int = SIGMA_ME
     K_out = np.zeros((B, H, cap_rows, d), np.float64)
     V_out = np.zeros((B, H, cap_rows, d), np.float64)
     w = np.empty((B, H, N), np.float64)
-    lib.kvm_ref_merge.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+    lib.kvm_ref_merge.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                        ctypes.c_double, ctypes.c_int] + [ctypes.c_void_p] * 8
-    rc = lib.kvm_ref_merge(B, H, N, d, _DTYPE[dtype], _ptr(sl), cap_rows, int(sigma_mode), float(sigma),
+    rc = lib.kvm_ref_merge(B, H, N, d, _DTYPE[dtype], _ptr(sl), cap_rows, int(weights), int(sigma_mode), float(sigma),
                            int(bool(value_scale_by_set_size)), _ptr(K), _ptr(V), _ptr(set_start), _ptr(pivot),
                            _ptr(n_sets), _ptr(K_out), _ptr(V_out), _ptr(w))
     if rc:

@@ -209,6 +209,17 @@ __device__ void block_select_kth_largest(KeyFn key_at, int count, int k, uint32_
     greater = gt;
 }
 
+// Random member of a set of m tokens that starts at token lo of a slice: the SplitMix64
+// output function (Steele, Lea, Flood 2014) at the counter seed + slice * 2^32 + lo, upper
+// 32 bits scaled to [0, m).
+__device__ __forceinline__ int random_member(uint64_t seed, int slice, int lo, int m) {
+    uint64_t z = seed + (((uint64_t)(uint32_t)slice << 32) | (uint32_t)lo) + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (int)(((z >> 32) * (uint64_t)m) >> 32);
+}
+
 struct SegArgs {
     const float *mass;
     const float *sim;
@@ -218,6 +229,8 @@ struct SegArgs {
     int H, N, cap_rows, enforce;
     double budget, recent_ratio, heavy_ratio;
     float threshold;
+    int pivot_rule;
+    uint64_t pivot_seed;
 };
 
 __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
@@ -427,6 +440,14 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
         set_start[s] = n;
         if (s < a.cap_rows) pivot[s] = -1;
     }
+    if (a.pivot_rule != KVM_PIVOT_MAX_SCORE) {
+        // the other pivot rules need only the sets' extents, which are complete now
+        __syncthreads();
+        for (int s = tid; s < min(M, a.cap_rows); s += SEG_BLOCK) {
+            const int lo = set_start[s], hi = set_start[s + 1];
+            pivot[s] = a.pivot_rule == KVM_PIVOT_LAST ? hi - 1 : lo + random_member(a.pivot_seed, slice, lo, hi - lo);
+        }
+    }
     if (M > a.cap_rows) status |= KVM_SLICE_TRUNCATED;
     if (tid == 0) {
         a.n_sets[slice] = M;
@@ -481,6 +502,8 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
     a.recent_ratio = pr.recent_ratio;
     a.heavy_ratio = pr.heavy_ratio;
     a.threshold = pr.threshold;
+    a.pivot_rule = pr.pivot_rule;
+    a.pivot_seed = pr.pivot_seed;
     ProfScope prof("segment_kernel", st);
     hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), 0, st, a);
     return check_launch("segment_kernel");

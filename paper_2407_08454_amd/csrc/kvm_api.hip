@@ -94,6 +94,14 @@ static kvm_status check_params(const kvm_params *pr, const char *fn)
         set_error("%s: unknown sigma_mode %d", fn, pr->sigma_mode);
         return KVM_ERR_UNSUPPORTED;
     }
+    if (pr->weights != KVM_WEIGHTS_GAUSSIAN && pr->weights != KVM_WEIGHTS_AVERAGE) {
+        set_error("%s: unknown weights %d", fn, pr->weights);
+        return KVM_ERR_UNSUPPORTED;
+    }
+    if (pr->pivot_rule < KVM_PIVOT_MAX_SCORE || pr->pivot_rule > KVM_PIVOT_RANDOM) {
+        set_error("%s: unknown pivot_rule %d", fn, pr->pivot_rule);
+        return KVM_ERR_UNSUPPORTED;
+    }
     if (pr->sigma_mode == KVM_SIGMA_FIXED && !(pr->sigma > 0.f)) {
         set_error("%s: fixed sigma must be > 0 (%g)", fn, (double)pr->sigma);
         return KVM_ERR_INVALID_ARG;
@@ -138,6 +146,9 @@ kvm_status kvm_params_for_budget(double budget, kvm_params *out)
     out->sigma = 0.f;
     out->value_scale_by_set_size = 1;
     out->enforce_budget = 1;
+    out->weights = KVM_WEIGHTS_GAUSSIAN;
+    out->pivot_rule = KVM_PIVOT_MAX_SCORE;
+    out->pivot_seed = 0;
     return KVM_OK;
 }
 

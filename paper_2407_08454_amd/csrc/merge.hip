@@ -28,7 +28,7 @@ struct MergeArgs {
     float *w_opt;
     const int32_t *plan;    // (slices, tiles_per_slice + 1): first set starting at or after each tile
     int H, N, cap_rows, tiles_per_slice;
-    int sigma_fixed;        // 1: use inv_two_sigma_sq
+    int mode;               // MERGE_ADAPTIVE, MERGE_FIXED (uses inv_two_sigma_sq) or MERGE_AVERAGE
     float inv_two_sigma_sq; // 1 / (2 sigma^2) for the fixed-sigma mode
     int value_scale;
 };
@@ -62,10 +62,13 @@ __device__ __forceinline__ float sq_dist16(const float *kp, const float *x) {
     return row16_sum((s0 + s1) + (s2 + s3));
 }
 
-// WITH_W: also write the per-token weights; FIXED: sigma given instead of derived from the
-// set.  Both are compile-time so that the row loops stay free of branches and the compiler
-// can interleave the independent rows.
-template <typename T, bool WITH_W, bool FIXED>
+// WITH_W: also write the per-token weights.  MODE: how the weights are formed -- Gaussian
+// kernel with sigma derived from the set, Gaussian kernel with a given sigma, or uniform
+// (average weighted merging).  Both are compile-time so that the row loops stay free of
+// branches and the compiler can interleave the independent rows.
+enum { MERGE_ADAPTIVE = 0, MERGE_FIXED = 1, MERGE_AVERAGE = 2 };
+
+template <typename T, bool WITH_W, int MODE>
 __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict__ K, const T *__restrict__ V,
                                                             T *__restrict__ K_out, T *__restrict__ V_out, MergeArgs a)
 {
@@ -174,12 +177,13 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
                 const int row = j0 + 4 * u + slot;
                 float x[8], v[8];
                 E::to_float(kr[u], x);
-                const float sq = sq_dist16(kp, x);
                 float g;
-                if (FIXED) {
-                    g = __expf(-sq * a.inv_two_sigma_sq);
+                if (MODE == MERGE_AVERAGE) {
+                    g = 1.f;
+                } else if (MODE == MERGE_FIXED) {
+                    g = __expf(-sq_dist16(kp, x) * a.inv_two_sigma_sq);
                 } else {
-                    const float r = __builtin_amdgcn_sqrtf(sq) * inv_mean;
+                    const float r = __builtin_amdgcn_sqrtf(sq_dist16(kp, x)) * inv_mean;
                     g = __expf(-r * r);
                 }
                 g = row < hi ? g : 0.f;
@@ -197,20 +201,24 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
             load_rows(Ks, lo, k0);
             load_rows(Vs, lo, v0);
             E::to_float(kp_raw, kp);
-            const float dsum = rows4_sum(distances(lo, k0));
-            inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
+            if (MODE == MERGE_ADAPTIVE) {
+                const float dsum = rows4_sum(distances(lo, k0));
+                inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
+            }
             accumulate(lo, k0, v0);
         } else {
-            // sweep 1: sum of the distances to the pivot
-            float dsum = 0.f;
-            for (int j0 = lo; j0 < hi; j0 += 4 * U) {
-                Raw kr[U];
-                load_rows(Ks, j0, kr);
-                if (j0 == lo) E::to_float(kp_raw, kp);
-                dsum += distances(j0, kr);
+            E::to_float(kp_raw, kp);
+            if (MODE == MERGE_ADAPTIVE) {
+                // sweep 1: sum of the distances to the pivot
+                float dsum = 0.f;
+                for (int j0 = lo; j0 < hi; j0 += 4 * U) {
+                    Raw kr[U];
+                    load_rows(Ks, j0, kr);
+                    dsum += distances(j0, kr);
+                }
+                dsum = rows4_sum(dsum);
+                inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
             }
-            dsum = rows4_sum(dsum);
-            inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
             // sweep 2: weights and weighted sums (K again, now from L2; V for the first time)
             for (int j0 = lo; j0 < hi; j0 += 4 * U) {
                 Raw kr[U], vr[U];
@@ -246,11 +254,13 @@ static void launch_merge_t(const kvm_shape &sh, const void *K, const void *V, vo
     const T *k = (const T *)K, *v = (const T *)V;
     T *ko = (T *)K_out, *vo = (T *)V_out;
     if (a.w_opt) {
-        if (a.sigma_fixed) hipLaunchKernelGGL((merge_kernel<T, true, true>), grid, block, 0, st, k, v, ko, vo, a);
-        else hipLaunchKernelGGL((merge_kernel<T, true, false>), grid, block, 0, st, k, v, ko, vo, a);
+        if (a.mode == MERGE_AVERAGE) hipLaunchKernelGGL((merge_kernel<T, true, MERGE_AVERAGE>), grid, block, 0, st, k, v, ko, vo, a);
+        else if (a.mode == MERGE_FIXED) hipLaunchKernelGGL((merge_kernel<T, true, MERGE_FIXED>), grid, block, 0, st, k, v, ko, vo, a);
+        else hipLaunchKernelGGL((merge_kernel<T, true, MERGE_ADAPTIVE>), grid, block, 0, st, k, v, ko, vo, a);
     } else {
-        if (a.sigma_fixed) hipLaunchKernelGGL((merge_kernel<T, false, true>), grid, block, 0, st, k, v, ko, vo, a);
-        else hipLaunchKernelGGL((merge_kernel<T, false, false>), grid, block, 0, st, k, v, ko, vo, a);
+        if (a.mode == MERGE_AVERAGE) hipLaunchKernelGGL((merge_kernel<T, false, MERGE_AVERAGE>), grid, block, 0, st, k, v, ko, vo, a);
+        else if (a.mode == MERGE_FIXED) hipLaunchKernelGGL((merge_kernel<T, false, MERGE_FIXED>), grid, block, 0, st, k, v, ko, vo, a);
+        else hipLaunchKernelGGL((merge_kernel<T, false, MERGE_ADAPTIVE>), grid, block, 0, st, k, v, ko, vo, a);
     }
 }
 
@@ -276,8 +286,8 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     a.N = sh.N;
     a.cap_rows = cap_rows;
     a.tiles_per_slice = (sh.N + MERGE_TILE - 1) / MERGE_TILE;
-    a.sigma_fixed = pr.sigma_mode == KVM_SIGMA_FIXED;
-    a.inv_two_sigma_sq = a.sigma_fixed ? 1.f / (2.f * pr.sigma * pr.sigma) : 0.f;
+    a.mode = pr.weights == KVM_WEIGHTS_AVERAGE ? MERGE_AVERAGE : (pr.sigma_mode == KVM_SIGMA_FIXED ? MERGE_FIXED : MERGE_ADAPTIVE);
+    a.inv_two_sigma_sq = a.mode == MERGE_FIXED ? 1.f / (2.f * pr.sigma * pr.sigma) : 0.f;
     a.value_scale = pr.value_scale_by_set_size;
     {
         ProfScope prof("merge_plan_kernel", st);

@@ -103,7 +103,8 @@ def _identify_both(K, mass64, dtype, params, lens=None):
     B, H, N, _ = K.shape
     g = gu.gpu_identify(K, mass32, dtype, params, lens)
     o = ref.identify_sets(K, mass32.astype(np.float64), dtype, params.budget, params.recent_ratio,
-                          params.heavy_ratio, params.threshold, bool(params.enforce_budget), g["cap_rows"], lens)
+                          params.heavy_ratio, params.threshold, bool(params.enforce_budget), g["cap_rows"], lens,
+                          pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed)
     return g, o
 
 
@@ -240,7 +241,7 @@ def test_identify_infeasible_budget_is_reported():
 def _merge_both(K, V, dtype, params, o, lens=None):
     ko, vo, w, Kt, Vt = gu.gpu_merge(K, V, dtype, params, o["set_start"], o["pivot"], o["n_sets"], lens)
     rk, rv, rw = ref.merge(K, V, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
-                           bool(params.value_scale_by_set_size), lens)
+                           bool(params.value_scale_by_set_size), lens, weights=params.weights)
     return ko, vo, w, rk, rv, rw, Kt, Vt
 
 
@@ -289,6 +290,40 @@ def test_merge_on_workload_slices(dtype, budget):
     errs = _check_merge(K, V, dtype, o, *res, f"{dtype} budget {budget}")
     _say(f"  worst K/V/w errors {errs[0]:.2e} {errs[1]:.2e} {errs[2]:.2e}; "
          f"largest set {int(np.diff(o['set_start'][0, 0, :o['n_sets'][0, 0] + 1]).max())}")
+
+
+@pytest.mark.parametrize("rule,seed", [(kb.KVM_PIVOT_LAST, 0), (kb.KVM_PIVOT_RANDOM, 0), (kb.KVM_PIVOT_RANDOM, 2 ** 63 + 12345)])
+@pytest.mark.parametrize("dtype,n", [("f16", 4096), ("bf16", 777)])
+def test_identify_pivot_rules(rule, seed, dtype, n):
+    _say(f"identify: pivot rule {rule}, seed {seed}, {dtype} n={n}")
+    Q, K, V = _slices(23, 2, 3, [n, n - 5], n, 128, 1, dtype)
+    mass = np.random.default_rng(n).random((2, 3, n)) + 0.01
+    for budget, thr, enforce in ((0.5, 0.75, True), (0.2, 0.95, True), (1.0, 0.6, False)):   # plain, fallback + truncation, free
+        params = kb.make_params(budget, 0.3 * budget, 0.2 * budget, threshold=thr, enforce_budget=enforce,
+                                pivot_rule=rule, pivot_seed=seed)
+        g, o = _identify_both(K, mass, dtype, params, [n, n - 5])
+        gu.compare_maps(g, o, [n, n - 5], n, params.threshold, f"pivot rule {rule} budget {budget}")
+        gu.check_partition(g, [n, n - 5], n, g["cap_rows"])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("scale", [True, False])
+def test_merge_average_weights(dtype, scale):
+    n = 1500
+    _say(f"merge: average weights, {dtype}, value scale {scale}")
+    Q, K, V = _slices(34, 1, 3, [n], n, 128, 1, dtype)
+    mass = np.random.default_rng(7).random((1, 3, n)) + 0.01
+    params = kb.make_params(0.5, 0.17, 0.12, weights=kb.KVM_WEIGHTS_AVERAGE, pivot_rule=kb.KVM_PIVOT_LAST,
+                            value_scale_by_set_size=scale)
+    o = ref.identify_sets(K, mass, dtype, 0.5, 0.17, 0.12, 0.75, True, n // 2, pivot_rule=ref.PIVOT_LAST)
+    res = _merge_both(K, V, dtype, params, o)
+    _check_merge(K, V, dtype, o, *res, f"average {dtype}")
+    # one long set (two sweeps in the kernel) and the fixed-sigma field set at the same time: ignored
+    params = kb.make_params(1.0, 0.0, 0.0, threshold=-2.0, enforce_budget=False, weights=kb.KVM_WEIGHTS_AVERAGE,
+                            sigma_mode=kb.KVM_SIGMA_FIXED, sigma=0.01, value_scale_by_set_size=scale)
+    o = ref.identify_sets(K, mass, dtype, 1.0, 0.0, 0.0, -2.0, False, n)
+    res = _merge_both(K, V, dtype, params, o)
+    _check_merge(K, V, dtype, o, *res, f"average, one set, {dtype}")
 
 
 @pytest.mark.parametrize("mode", ["fixed_sigma", "no_value_scale", "fixed_sigma_small"])
@@ -377,16 +412,27 @@ def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
         m32 = m_o.astype(np.float32)
         gi = gu.gpu_identify(Ks, m32, dtype, params, ls)
         oi = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
-                               params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"], ls)
+                               params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"], ls,
+                               pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed)
         gu.compare_maps(gi, oi, ls, N, params.threshold, f"{what} ({b},{h})")
         res = _merge_both(Ks, Vs, dtype, params, oi, ls)
         _check_merge(Ks, Vs, dtype, oi, *res, f"{what} ({b},{h})")
         # end to end: GPU maps from GPU mass against oracle maps from oracle mass
-        same = all(np.array_equal(g[k][b, h], oi[k][0, 0]) for k in ("set_id", "set_start", "pivot"))
+        oe = oi
+        if params.pivot_rule == kb.KVM_PIVOT_RANDOM:         # the draws depend on the slice's index in the call
+            oe = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
+                                   params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"],
+                                   ls, pivot_rule=params.pivot_rule,
+                                   pivot_seed=(params.pivot_seed + ((b * H + h) << 32)) % (1 << 64))
+        same = all(np.array_equal(g[k][b, h], oe[k][0, 0]) for k in ("set_id", "set_start", "pivot"))
         if same:
             M = min(int(oi["n_sets"][0, 0]), buf.cap)
-            ek = gu.row_rel_err(gu.to_host_f64(buf.K_out[b, h, :M]), res[3][0, 0, :M]).max() if M else 0.0
-            ev = gu.row_rel_err(gu.to_host_f64(buf.V_out[b, h, :M]), res[4][0, 0, :M]).max() if M else 0.0
+            rk, rv = res[3], res[4]
+            if oe is not oi:
+                rk, rv, _ = ref.merge(Ks, Vs, dtype, oe["set_start"], oe["pivot"], oe["n_sets"], params.sigma_mode,
+                                      params.sigma, bool(params.value_scale_by_set_size), ls, weights=params.weights)
+            ek = gu.row_rel_err(gu.to_host_f64(buf.K_out[b, h, :M]), rk[0, 0, :M]).max() if M else 0.0
+            ev = gu.row_rel_err(gu.to_host_f64(buf.V_out[b, h, :M]), rv[0, 0, :M]).max() if M else 0.0
             assert ek <= gu.kv_tol(dtype) and ev <= gu.kv_tol(dtype), \
                 f"{what} ({b},{h}): end-to-end K/V error {ek:.2e}/{ev:.2e}"
         else:
@@ -456,3 +502,21 @@ def test_whole_pass_config2_full_size_sampled():
     tot = mass.double().sum(-1).cpu().numpy()
     assert np.abs(tot / N - 1).max() <= 1e-5, f"scores of a slice do not sum to n: {np.abs(tot / N - 1).max():.2e}"
     assert (mass[:, :, 0] >= 1).all() and (mass[:, :, N - 1] <= 1).all() and (mass > 0).all()
+
+
+@pytest.mark.parametrize("variant", ["average_last", "gaussian_random", "fixed_sigma"])
+def test_whole_pass_variants(variant):
+    """The configurations the paper compares its method with (Section 4.2 first experiment,
+    Section 5.4), end to end on two layers of the headline shape."""
+    cfg = synth.CONFIGS[2]
+    _say(f"whole pass: variant {variant}")
+    Q, K, V, lens = synth.gen_config(cfg, layers=2)
+    params = kb.kvm_params_for_budget(0.5)
+    if variant == "average_last":
+        params.weights, params.pivot_rule = kb.KVM_WEIGHTS_AVERAGE, kb.KVM_PIVOT_LAST
+    elif variant == "gaussian_random":
+        params.pivot_rule, params.pivot_seed = kb.KVM_PIVOT_RANDOM, 2024
+    else:
+        params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, 5.0
+    g = _whole_pass(Q, K, V, "f16", 1, params, lens, [(0, 0), (1, 31)], variant)
+    assert (g["n_sets"] <= cfg["N"] // 2).all()
