@@ -49,6 +49,8 @@ def main() -> int:
                     help="merge weights (average = the average weighted merging of Section 4.2)")
     ap.add_argument("--pivot", choices=["max-score", "last", "random"], default="max-score",
                     help="pivot rule (last = largest index, Section 4.2; random = Section 5.4)")
+    ap.add_argument("--sets", choices=["adjacent", "anchor"], default="adjacent",
+                    help="reading of Algorithm 1 (anchor = similarity to the set's top token; no budget fallback)")
     ap.add_argument("--sigma", type=float, default=None, help="fixed sigma (Section 5.4) instead of the per-set one")
     ap.add_argument("--gen-workers", type=int, default=None,
                     help="processes that generate the inputs (1 = in this process, e.g. under a profiler)")
@@ -90,7 +92,10 @@ def main() -> int:
                          "random": kb.KVM_PIVOT_RANDOM}[args.pivot]
     if args.sigma is not None:
         params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, args.sigma
-    variant = f"weights {args.weights}, pivot {args.pivot}, sigma {'per set' if args.sigma is None else args.sigma}"
+    if args.sets == "anchor":
+        params.set_rule = kb.KVM_SETS_ANCHOR
+    variant = (f"sets {args.sets}, weights {args.weights}, pivot {args.pivot}, "
+               f"sigma {'per set' if args.sigma is None else args.sigma}")
     shape = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(shape, params, "cuda", tdt)
 
@@ -139,7 +144,7 @@ def main() -> int:
     roofline = None
     hbm = {}
     headline = (args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
-                and args.pivot == "max-score" and args.sigma is None)
+                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent")
 
     def traffic(name):
         return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None
@@ -177,7 +182,7 @@ def main() -> int:
         m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
         o = ref.identify_sets(Ks, m.astype(np.float32).astype(np.float64), dtype, params.budget, params.recent_ratio,
                               params.heavy_ratio, params.threshold, True, buf.cap, ls, pivot_rule=params.pivot_rule,
-                              pivot_seed=params.pivot_seed)
+                              pivot_seed=params.pivot_seed, set_rule=params.set_rule)
         ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
                   bool(params.value_scale_by_set_size), seq_lens=ls, weights=params.weights)
         cpu_s = time.perf_counter() - t0

@@ -74,6 +74,15 @@ typedef enum {
     KVM_PIVOT_RANDOM = 2      /* drawn at random (Section 5.4, "Choice of Pivotal State")     */
 } kvm_pivot_rule;
 
+/* How Algorithm 1 grows a set. */
+typedef enum {
+    KVM_SETS_ADJACENT = 0,    /* a token joins the set of its successor iff the two are
+                                 similar enough (chain of adjacent tokens)                    */
+    KVM_SETS_ANCHOR = 1       /* tokens below the set's top token join, one after the other,
+                                 as long as they are similar enough to that top token
+                                 (Section 3.2: the states similar to "a given key state")     */
+} kvm_set_rule;
+
 typedef struct {
     int32_t B;                /* batch (x layers): every (b, h) slice is independent         */
     int32_t H_kv;             /* KV heads                                                     */
@@ -96,6 +105,8 @@ typedef struct {
     int32_t weights;          /* kvm_weights                                                  */
     int32_t pivot_rule;       /* kvm_pivot_rule                                               */
     uint64_t pivot_seed;      /* seed of the draws of KVM_PIVOT_RANDOM                        */
+    int32_t set_rule;         /* kvm_set_rule                                                 */
+    int32_t reserved;         /* set to 0                                                     */
 } kvm_params;
 
 /*
@@ -104,7 +115,8 @@ typedef struct {
  * 0.75 for both (the proportions are read as fractions of the length).  Other
  * budgets in (0,1] get recent = 0.34 beta, heavy = 0.24 beta (the 0.50 row
  * scaled).  Sets sigma_mode = MEAN_DIST, value_scale_by_set_size = 1,
- * enforce_budget = 1, weights = GAUSSIAN, pivot_rule = MAX_SCORE, pivot_seed = 0.
+ * enforce_budget = 1, weights = GAUSSIAN, pivot_rule = MAX_SCORE, pivot_seed = 0,
+ * set_rule = ADJACENT.
  * Host call.  KVM_ERR_INVALID_ARG if out == NULL or budget
  * is not in (0,1].
  */
@@ -162,6 +174,12 @@ kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, f
  *      for a set of m tokens, u = upper 32 bits of the SplitMix64 output function at the
  *      counter pivot_seed + (slice index b*H_kv+h) * 2^32 + first token (mod 2^64), so the
  *      draws can be reproduced anywhere.
+ * With set_rule == KVM_SETS_ANCHOR steps 3 and 4 read: walking down from the last
+ * token, the set of token i takes tokens i-1, i-2, ... while they are not conserved and
+ * their cosine similarity to k_i exceeds the threshold; the first token that does not
+ * join starts the next set.  This reading has no budget fallback: a slice with
+ * M > floor(budget n) gets KVM_SLICE_INFEASIBLE (when enforce_budget is set) and is
+ * truncated to the capacity.  sim_opt still holds the adjacent similarities.
  *   K            in   (B, H_kv, N, d)
  *   mass         in   (B, H_kv, N) float32 (finite; as written by kvm_attn_mass)
  *   set_id       out  (B, H_kv, N) int32: set of token j, -1 at positions >= n

@@ -24,6 +24,11 @@
  *         (Section 5.2 averages them; a constant factor changes no decision).
  *   R-b1  Algorithm 1 is an adjacent chain: token i-1 joins the set of token i
  *         iff their cosine similarity exceeds the threshold; then i moves down.
+ *         The other reading is available as a variant (REF_SETS_ANCHOR): the set of
+ *         token i takes the tokens below it, one after the other, as long as their
+ *         similarity to k_i itself exceeds the threshold (Section 3.2 speaks of the
+ *         states similar to "a given key state"); the first token that fails becomes
+ *         the next i.  No budget fallback exists for this reading.
  *   R-b3  a zero-norm key has similarity 0 to its neighbours.
  *   R-b4  conserved tokens are singleton sets in their original position and
  *         split the run around them.
@@ -62,6 +67,7 @@ enum { REF_SLICE_OK = 0, REF_SLICE_FALLBACK = 1, REF_SLICE_INFEASIBLE = 2, REF_S
 enum { REF_SIGMA_MEAN_DIST = 0, REF_SIGMA_FIXED = 1 };
 enum { REF_WEIGHTS_GAUSSIAN = 0, REF_WEIGHTS_AVERAGE = 1 };
 enum { REF_PIVOT_MAX_SCORE = 0, REF_PIVOT_LAST = 1, REF_PIVOT_RANDOM = 2 };
+enum { REF_SETS_ADJACENT = 0, REF_SETS_ANCHOR = 1 };
 
 /* ---- exact widening of storage types ------------------------------------ */
 
@@ -237,6 +243,33 @@ static int walk_sets(int n, const unsigned char *joins, int *first)
     return m;
 }
 
+/* Algorithm 1 with the similarity taken to the set's own top token k_i (the anchor):
+ * tokens i-1, i-2, ... join while they are not conserved and delta(k_i, k_j) > epsilon;
+ * then "i = j" moves on to the first token that did not join.  Same outputs as walk_sets.
+ * *margin = smallest |delta - epsilon| over all comparisons made (how close any decision
+ * came to the threshold). */
+static int walk_sets_anchor(int n, int d, const double *k, const unsigned char *prot, double threshold,
+                            int *first, double *margin)
+{
+    int m = 0, i = n - 1;
+    *margin = INFINITY;
+    while (i >= 0) {
+        int j = i;
+        if (!prot[i]) {
+            while (j >= 1 && !prot[j - 1]) {
+                double c = cosine(k + (size_t)i * d, k + (size_t)(j - 1) * d, d);
+                double gap = fabs(c - threshold);
+                if (gap < *margin) *margin = gap;
+                if (!(c > threshold)) break;
+                --j;
+            }
+        }
+        first[m++] = j;
+        i = j - 1;
+    }
+    return m;
+}
+
 /*
  * K: (B, H, N, d) storage dtype; mass: (B, H, N) fp64 (the caller widens the
  * fp32 values the GPU path reads, so both sides rank identical numbers).
@@ -255,15 +288,16 @@ static int walk_sets(int n, const unsigned char *joins, int *first)
  */
 int kvm_ref_identify_sets(int B, int H, int N, int d, int dtype, const int32_t *seq_lens,
                           double budget, double recent_ratio, double heavy_ratio, double threshold,
-                          int enforce_budget, int pivot_rule, uint64_t pivot_seed, int cap_rows, const void *K,
-                          const double *mass,
+                          int enforce_budget, int set_rule, int pivot_rule, uint64_t pivot_seed, int cap_rows,
+                          const void *K, const double *mass,
                           int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets,
                           int32_t *slice_status, double *sim_out, unsigned char *protected_out,
-                          double *min_removed_sim)
+                          double *min_removed_sim, double *anchor_margin)
 {
     int bh;
     if (B < 0 || H < 1 || N < 0 || d < 1 || cap_rows < 0) return 1;
     if (pivot_rule < REF_PIVOT_MAX_SCORE || pivot_rule > REF_PIVOT_RANDOM) return 1;
+    if (set_rule != REF_SETS_ADJACENT && set_rule != REF_SETS_ANCHOR) return 1;
     if (!set_id || !set_start || !pivot || !n_sets || !slice_status) return 1;
     if (B && N && (!K || !mass)) return 1;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -305,9 +339,15 @@ int kvm_ref_identify_sets(int B, int H, int N, int d, int dtype, const int32_t *
         /* Algorithm 1: j-1 joins j iff delta > epsilon (strict) and neither is conserved */
         for (j = 1; j < n; ++j) joins[j] = (!prot[j - 1] && !prot[j] && sim[j] > threshold) ? 1 : 0;
         M = walk_sets(n, joins, first);
+        if (set_rule == REF_SETS_ANCHOR) {
+            double margin;
+            M = walk_sets_anchor(n, d, kd, prot, threshold, first, &margin);
+            if (anchor_margin) anchor_margin[bh] = margin;
+            if (enforce_budget && M > cap) status |= REF_SLICE_INFEASIBLE; /* no fallback for this reading */
+        }
 
         /* [reading] R-b6: budget fallback */
-        if (enforce_budget && M > cap) {
+        if (set_rule == REF_SETS_ADJACENT && enforce_budget && M > cap) {
             int n_nat = 0, r = M - cap;
             for (j = 1; j < n; ++j)
                 if (!joins[j] && !prot[j - 1] && !prot[j]) { rk[n_nat].v = sim[j]; rk[n_nat].idx = j; ++n_nat; }

@@ -22,6 +22,7 @@ SLICE_OK, SLICE_FALLBACK, SLICE_INFEASIBLE, SLICE_TRUNCATED = 0, 1, 2, 4
 SIGMA_MEAN_DIST, SIGMA_FIXED = 0, 1
 WEIGHTS_GAUSSIAN, WEIGHTS_AVERAGE = 0, 1
 PIVOT_MAX_SCORE, PIVOT_LAST, PIVOT_RANDOM = 0, 1, 2
+SETS_ADJACENT, SETS_ANCHOR = 0, 1
 
 _lib = None
 
@@ -106,7 +107,8 @@ def attn_mass(Q, K, dtype: str, G: int = 1, seq_lens=None):
 
 def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy_ratio: float,
                   threshold: float, enforce_budget: bool = True, cap_rows: int | None = None,
-                  seq_lens=None, pivot_rule: int = PIVOT_MAX_SCORE, pivot_seed: int = 0):
+                  seq_lens=None, pivot_rule: int = PIVOT_MAX_SCORE, pivot_seed: int = 0,
+                  set_rule: int = SETS_ADJACENT):
     """K (B, H, N, d), mass (B, H, N) -> dict of index maps (see kvm_ref.c)."""
     lib = _load()
     _check_storage(K, dtype)
@@ -125,16 +127,18 @@ def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy
         sim=np.empty((B, H, N), np.float64),
         protected=np.empty((B, H, N), np.uint8),
         min_removed_sim=np.empty((B, H), np.float64),
+        anchor_margin=np.full((B, H), np.inf, np.float64),
         cap_rows=cap_rows,
     )
     lib.kvm_ref_identify_sets.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] + [ctypes.c_double] * 4 + \
-        [ctypes.c_int] * 2 + [ctypes.c_uint64, ctypes.c_int] + [ctypes.c_void_p] * 10
+        [ctypes.c_int] * 3 + [ctypes.c_uint64, ctypes.c_int] + [ctypes.c_void_p] * 11
     rc = lib.kvm_ref_identify_sets(B, H, N, d, _DTYPE[dtype], _ptr(sl), float(budget), float(recent_ratio),
-                                   float(heavy_ratio), float(threshold), int(bool(enforce_budget)), int(pivot_rule),
-                                   int(pivot_seed), cap_rows,
+                                   float(heavy_ratio), float(threshold), int(bool(enforce_budget)), int(set_rule),
+                                   int(pivot_rule), int(pivot_seed), cap_rows,
                                    _ptr(K), _ptr(mass), _ptr(out["set_id"]), _ptr(out["set_start"]),
                                    _ptr(out["pivot"]), _ptr(out["n_sets"]), _ptr(out["status"]),
-                                   _ptr(out["sim"]), _ptr(out["protected"]), _ptr(out["min_removed_sim"]))
+                                   _ptr(out["sim"]), _ptr(out["protected"]), _ptr(out["min_removed_sim"]),
+                                   _ptr(out["anchor_margin"]))
     if rc:
         raise RuntimeError(f"kvm_ref_identify_sets failed: {rc}")
     return out

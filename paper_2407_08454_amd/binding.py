@@ -21,6 +21,7 @@ KVM_SLICE_FALLBACK, KVM_SLICE_INFEASIBLE, KVM_SLICE_TRUNCATED = 1, 2, 4
 KVM_SIGMA_MEAN_DIST, KVM_SIGMA_FIXED = 0, 1
 KVM_WEIGHTS_GAUSSIAN, KVM_WEIGHTS_AVERAGE = 0, 1
 KVM_PIVOT_MAX_SCORE, KVM_PIVOT_LAST, KVM_PIVOT_RANDOM = 0, 1, 2
+KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
            "kvm_identify_sets", "kvm_merge", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
@@ -38,7 +39,8 @@ class KvmParams(ctypes.Structure):
     _fields_ = [("budget", ctypes.c_double), ("recent_ratio", ctypes.c_double), ("heavy_ratio", ctypes.c_double),
                 ("threshold", ctypes.c_float), ("sigma_mode", ctypes.c_int32), ("sigma", ctypes.c_float),
                 ("value_scale_by_set_size", ctypes.c_int32), ("enforce_budget", ctypes.c_int32),
-                ("weights", ctypes.c_int32), ("pivot_rule", ctypes.c_int32), ("pivot_seed", ctypes.c_uint64)]
+                ("weights", ctypes.c_int32), ("pivot_rule", ctypes.c_int32), ("pivot_seed", ctypes.c_uint64),
+                ("set_rule", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class KvmKernelTime(ctypes.Structure):
@@ -108,10 +110,10 @@ def kvm_params_for_budget(budget: float) -> KvmParams:
 
 def make_params(budget, recent_ratio, heavy_ratio, threshold=0.75, sigma_mode=KVM_SIGMA_MEAN_DIST, sigma=0.0,
                 value_scale_by_set_size=True, enforce_budget=True, weights=KVM_WEIGHTS_GAUSSIAN,
-                pivot_rule=KVM_PIVOT_MAX_SCORE, pivot_seed=0) -> KvmParams:
+                pivot_rule=KVM_PIVOT_MAX_SCORE, pivot_seed=0, set_rule=KVM_SETS_ADJACENT) -> KvmParams:
     return KvmParams(float(budget), float(recent_ratio), float(heavy_ratio), float(threshold), int(sigma_mode),
                      float(sigma), int(bool(value_scale_by_set_size)), int(bool(enforce_budget)), int(weights),
-                     int(pivot_rule), int(pivot_seed))
+                     int(pivot_rule), int(pivot_seed), int(set_rule), 0)
 
 
 def make_shape(K: torch.Tensor, G: int = 1, seq_lens: torch.Tensor | None = None) -> KvmShape:

@@ -1,9 +1,12 @@
 // Merging-set identification (Section 3.2; Section 4.1 Def. 4.1 and Algorithm 1;
 // conserved states: Section 4.1 last paragraph, Section 5.1; pivot: Section 4.2 Eq. (7)).
 //
-// Two kernels:
-//   cosine_scan_kernel  streams K once and writes sim[j] = cos(k_{j-1}, k_j) (Eq. (2));
-//                       HBM-bound, 16 lanes per 128-wide row, 16 B per lane.
+// Kernels:
+//   cosine_scan_kernel  streams K once and writes sim[j] = cos(k_{j-1}, k_j) (Eq. (2)) and the
+//                       inverse norm of every key; HBM-bound, 16 lanes per 128-wide row,
+//                       16 B per lane.
+//   anchor_run_kernel   (anchor reading of Algorithm 1 only) for every free token i, how many
+//                       free tokens directly below it are similar enough to k_i.
 //   segment_kernel      one workgroup per slice: exact top-k of the aggregated scores by
 //                       radix select, boundary flags, prefix scan to set ids, the budget
 //                       fallback, and a segmented arg-max scan for the pivots.  All integer
@@ -64,6 +67,7 @@ __device__ __forceinline__ float inv_norm(float nn) { return nn >= 1.17549435e-3
 
 template <typename T>
 __global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restrict__ K, float *__restrict__ sim,
+                                                                 float *__restrict__ inv_norm_out,
                                                                  const int32_t *__restrict__ seq_lens, int H, int N,
                                                                  int tiles_per_slice)
 {
@@ -80,7 +84,10 @@ __global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restr
     if (j_block >= n) {                                      // padding only: defined zeros, nothing read
         if (c == 0)
             for (int i = 0; i < COS_ROWS_PER_GROUP; ++i)
-                if (j0 + i < N) sims[j0 + i] = 0.f;
+                if (j0 + i < N) {
+                    sims[j0 + i] = 0.f;
+                    if (inv_norm_out) inv_norm_out[(size_t)slice * N + j0 + i] = 0.f;
+                }
         return;
     }
     const T *Ks = K + (size_t)slice * N * HEAD_DIM;
@@ -104,9 +111,71 @@ __global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restr
         const float r = inv_norm(row16_sum(RowDot<T>::dot(raw[i], raw[i])));
         // zero norm, first token of the sequence or padding: similarity 0
         const float s = (j > 0 && j < n) ? (dot * r) * r_prev : 0.f;
-        if (c == (i & 15) && j < N) sims[j] = s;
+        if (c == (i & 15) && j < N) {
+            sims[j] = s;
+            if (inv_norm_out) inv_norm_out[(size_t)slice * N + j] = j < n ? r : 0.f;
+        }
         prev = raw[i];
         r_prev = r;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// anchor rule: run lengths
+// ------------------------------------------------------------------------------------------
+
+constexpr int RUN_BLOCK = 256;
+constexpr int RUN_ANCHORS_PER_GROUP = 4;                    // anchors a 16-lane group handles in turn
+constexpr int RUN_TILE = (RUN_BLOCK / 16) * RUN_ANCHORS_PER_GROUP;
+constexpr int RUN_BATCH = 4;                                 // candidate rows in flight per group
+
+// run[i] = number of tokens i-1, i-2, ... directly below the free token i that are free and
+// whose cosine similarity to k_i exceeds eps, up to the first one that is not (0 for a
+// conserved token).  One 16-lane group per anchor; the rows come from L2, which the
+// neighbouring anchors keep warm.  flags bit 0 = conserved.
+template <typename T>
+__global__ __launch_bounds__(RUN_BLOCK) void anchor_run_kernel(const T *__restrict__ K, const float *__restrict__ inv_norm,
+                                                                const uint8_t *__restrict__ flags, int32_t *__restrict__ run,
+                                                                const int32_t *__restrict__ seq_lens, int H, int N,
+                                                                int tiles_per_slice, float eps)
+{
+    typedef typename Elem<T>::Raw Raw;
+    const int slice = blockIdx.x / tiles_per_slice;
+    const int tile = blockIdx.x - slice * tiles_per_slice;
+    const int n = clamp_len(seq_lens, slice / H, N);
+    const int c = threadIdx.x & 15, group = threadIdx.x >> 4;
+    const T *Ks = K + (size_t)slice * N * HEAD_DIM;
+    const float *rn = inv_norm + (size_t)slice * N;
+    const uint8_t *fl = flags + (size_t)slice * N;
+    int32_t *runs = run + (size_t)slice * N;
+    for (int a = 0; a < RUN_ANCHORS_PER_GROUP; ++a) {
+        const int i = tile * RUN_TILE + a * (RUN_BLOCK / 16) + group;
+        if (i >= n) continue;                                // (uniform within the group)
+        int count = 0;
+        if (!(fl[i] & 1)) {
+            const Raw anchor = Elem<T>::load(Ks + (size_t)i * HEAD_DIM, c);
+            const float ri = rn[i];
+            bool open = true;
+            for (int base = i - 1; base >= 0 && open; base -= RUN_BATCH) {
+                Raw row[RUN_BATCH];
+                float rj[RUN_BATCH];
+                bool free_j[RUN_BATCH];
+#pragma unroll
+                for (int u = 0; u < RUN_BATCH; ++u) {
+                    const int j = max(base - u, 0);
+                    row[u] = Elem<T>::load(Ks + (size_t)j * HEAD_DIM, c);
+                    rj[u] = rn[j];
+                    free_j[u] = base - u >= 0 && !(fl[j] & 1);
+                }
+#pragma unroll
+                for (int u = 0; u < RUN_BATCH; ++u) {
+                    const float cosv = (row16_sum(RowDot<T>::dot(anchor, row[u])) * ri) * rj[u];
+                    open = open && free_j[u] && cosv > eps;
+                    count += open ? 1 : 0;
+                }
+            }
+        }
+        if (c == 0) runs[i] = count;
     }
 }
 
@@ -231,7 +300,12 @@ struct SegArgs {
     float threshold;
     int pivot_rule;
     uint64_t pivot_seed;
+    const int32_t *run;       // anchor rule: run lengths
+    int set_rule;
+    int phase;                // SEG_ALL, or the two halves the anchor rule runs its own kernel between
+    int walk_in_lds;          // anchor rule: 3 N bytes of dynamic LDS hold the walk's inputs
 };
+enum { SEG_ALL = 0, SEG_FLAGS_ONLY = 1, SEG_AFTER_FLAGS = 2 };
 
 __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
 {
@@ -254,6 +328,7 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
     if (n_heavy > pre) n_heavy = pre;
     const int cap = (int)floor(a.budget * (double)n);
 
+    if (a.phase != SEG_AFTER_FLAGS) {
     for (int j = n + tid; j < a.N; j += SEG_BLOCK) set_id[j] = -1;
 
     // ---- conserved tokens: recent window + exact top-k of mass (ties: lower index) ----------
@@ -293,10 +368,55 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
             carry += total;
         }
     }
+    }
+    if (a.phase == SEG_FLAGS_ONLY) return;
     __syncthreads();
 
+    const bool anchor_rule = a.set_rule == KVM_SETS_ANCHOR;
+    if (anchor_rule) {
+        // Walk every stretch of free tokens down from its last token: the set of token i reaches
+        // run[i] tokens down, and the token below it is the next i.  Bit 2 marks a set's first
+        // token.  (One thread per stretch; a stretch costs one dependent load per set.)
+        const int32_t *run = a.run + (size_t)slice * a.N;
+        extern __shared__ uint16_t walk_lds[];               // run lengths, then the conserved bits
+        if (a.walk_in_lds) {
+            // a copy in LDS: the walk is a chain of dependent reads (a run length fits 16 bits
+            // whenever the copy fits LDS)
+            uint16_t *lrun = walk_lds;
+            uint8_t *lprot = reinterpret_cast<uint8_t *>(walk_lds + a.N);
+            for (int j = tid; j < n; j += SEG_BLOCK) {
+                lrun[j] = (uint16_t)min(max(run[j], 0), 65535);
+                lprot[j] = flags[j] & 1;
+            }
+            __syncthreads();
+            for (int e = tid; e < n; e += SEG_BLOCK) {
+                if (lprot[e] || (e + 1 < n && !lprot[e + 1])) continue;       // not the last token of a stretch
+                int i = e;
+                while (i >= 0 && !lprot[i]) {
+                    const int first = max(i - (int)lrun[i], 0);
+                    flags[first] = 4;                         // a free token: no other bit is set
+                    i = first - 1;
+                }
+            }
+        } else {
+            for (int e = tid; e < n; e += SEG_BLOCK) {
+                if ((flags[e] & 1) || (e + 1 < n && !(flags[e + 1] & 1))) continue;
+                int i = e;
+                while (i >= 0 && !(flags[i] & 1)) {
+                    const int first = max(i - max(run[i], 0), 0);
+                    flags[first] = 4;                         // a free token: no other bit is set
+                    i = first - 1;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
     // j-1 and j may share a set (before the budget rule); "natural" boundary = both free, sim <= eps
-    auto joins = [&](int j) -> bool { return j >= 1 && !(flags[j] & 1) && !(flags[j - 1] & 1) && sim[j] > eps; };
+    auto joins = [&](int j) -> bool {
+        if (anchor_rule) return j >= 1 && !(flags[j] & 5);   // neither conserved nor a set's first token
+        return j >= 1 && !(flags[j] & 1) && !(flags[j - 1] & 1) && sim[j] > eps;
+    };
     auto natural = [&](int j) -> bool { return j >= 1 && !(flags[j] & 1) && !(flags[j - 1] & 1) && !(sim[j] > eps); };
 
     // ---- count sets and natural boundaries ----------------------------------------------------
@@ -310,7 +430,8 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
     int status = 0;
 
     // ---- budget fallback: remove the most similar natural boundaries (ties: higher index) -----
-    if (a.enforce && M0 > cap) {
+    if (anchor_rule && a.enforce && M0 > cap) status |= KVM_SLICE_INFEASIBLE;   // no fallback for this rule
+    if (!anchor_rule && a.enforce && M0 > cap) {
         const int r = M0 - cap;
         bool all = n_nat <= r;
         uint32_t T2 = 0;
@@ -460,26 +581,39 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
 // ------------------------------------------------------------------------------------------
 
 template <typename T>
-static void launch_cosine(const kvm_shape &sh, const void *K, float *sim, hipStream_t st)
+static void launch_cosine(const kvm_shape &sh, const void *K, float *sim, float *inv_norm, hipStream_t st)
 {
     const int tiles = (sh.N + COS_ROWS_PER_BLOCK - 1) / COS_ROWS_PER_BLOCK;
     const long long blocks = (long long)sh.B * sh.H_kv * tiles;
     ProfScope prof("cosine_scan_kernel", st);
-    hipLaunchKernelGGL(cosine_scan_kernel<T>, dim3((unsigned)blocks), dim3(COS_BLOCK), 0, st, (const T *)K, sim,
+    hipLaunchKernelGGL(cosine_scan_kernel<T>, dim3((unsigned)blocks), dim3(COS_BLOCK), 0, st, (const T *)K, sim, inv_norm,
                        sh.seq_lens, sh.H_kv, sh.N, tiles);
+}
+
+template <typename T>
+static void launch_anchor_run(const kvm_shape &sh, const void *K, const float *inv_norm, const uint8_t *flags,
+                              int32_t *run, float eps, hipStream_t st)
+{
+    const int tiles = (sh.N + RUN_TILE - 1) / RUN_TILE;
+    const long long blocks = (long long)sh.B * sh.H_kv * tiles;
+    ProfScope prof("anchor_run_kernel", st);
+    hipLaunchKernelGGL(anchor_run_kernel<T>, dim3((unsigned)blocks), dim3(RUN_BLOCK), 0, st, (const T *)K, inv_norm, flags,
+                       run, sh.seq_lens, sh.H_kv, sh.N, tiles, eps);
 }
 
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const float *mass,
                            int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets, float *sim,
-                           uint8_t *flags, int32_t *slice_status, hipStream_t st)
+                           float *inv_norm, int32_t *run, uint8_t *flags, int32_t *slice_status, hipStream_t st)
 {
     const long long slices = (long long)sh.B * sh.H_kv;
     if (slices == 0) return KVM_OK;
+    const bool anchor = pr.set_rule == KVM_SETS_ANCHOR;
     if (sh.N > 0) {
+        float *rn = anchor ? inv_norm : nullptr;
         switch (sh.dtype) {
-        case KVM_F32: launch_cosine<float>(sh, K, sim, st); break;
-        case KVM_F16: launch_cosine<half_t>(sh, K, sim, st); break;
-        default: launch_cosine<bf16_t>(sh, K, sim, st); break;
+        case KVM_F32: launch_cosine<float>(sh, K, sim, rn, st); break;
+        case KVM_F16: launch_cosine<half_t>(sh, K, sim, rn, st); break;
+        default: launch_cosine<bf16_t>(sh, K, sim, rn, st); break;
         }
         kvm_status rc = check_launch("cosine_scan_kernel");
         if (rc != KVM_OK) return rc;
@@ -504,8 +638,36 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
     a.threshold = pr.threshold;
     a.pivot_rule = pr.pivot_rule;
     a.pivot_seed = pr.pivot_seed;
+    a.run = run;
+    a.set_rule = pr.set_rule;
+    a.phase = SEG_ALL;
+    a.walk_in_lds = 0;
+    size_t walk_lds_bytes = 0;
+    if (anchor && sh.N > 0) {
+        // the conserved tokens first, then the run lengths (which stop at conserved tokens),
+        // then the walk over the runs and everything after it
+        a.phase = SEG_FLAGS_ONLY;
+        {
+            ProfScope prof("segment_kernel", st);
+            hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), 0, st, a);
+        }
+        kvm_status rc = check_launch("segment_kernel");
+        if (rc != KVM_OK) return rc;
+        switch (sh.dtype) {
+        case KVM_F32: launch_anchor_run<float>(sh, K, inv_norm, flags, run, pr.threshold, st); break;
+        case KVM_F16: launch_anchor_run<half_t>(sh, K, inv_norm, flags, run, pr.threshold, st); break;
+        default: launch_anchor_run<bf16_t>(sh, K, inv_norm, flags, run, pr.threshold, st); break;
+        }
+        rc = check_launch("anchor_run_kernel");
+        if (rc != KVM_OK) return rc;
+        a.phase = SEG_AFTER_FLAGS;
+        if (sh.N <= 16384) {
+            a.walk_in_lds = 1;
+            walk_lds_bytes = (size_t)sh.N * 3;
+        }
+    }
     ProfScope prof("segment_kernel", st);
-    hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), 0, st, a);
+    hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), walk_lds_bytes, st, a);
     return check_launch("segment_kernel");
 }
 

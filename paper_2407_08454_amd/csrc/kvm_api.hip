@@ -98,6 +98,10 @@ static kvm_status check_params(const kvm_params *pr, const char *fn)
         set_error("%s: unknown weights %d", fn, pr->weights);
         return KVM_ERR_UNSUPPORTED;
     }
+    if (pr->set_rule != KVM_SETS_ADJACENT && pr->set_rule != KVM_SETS_ANCHOR) {
+        set_error("%s: unknown set_rule %d", fn, pr->set_rule);
+        return KVM_ERR_UNSUPPORTED;
+    }
     if (pr->pivot_rule < KVM_PIVOT_MAX_SCORE || pr->pivot_rule > KVM_PIVOT_RANDOM) {
         set_error("%s: unknown pivot_rule %d", fn, pr->pivot_rule);
         return KVM_ERR_UNSUPPORTED;
@@ -121,7 +125,8 @@ static size_t ws_attn(const kvm_shape *sh)
 static size_t ws_identify(const kvm_shape *sh)
 {
     const size_t tok = (size_t)sh->B * sh->H_kv * sh->N;
-    return align_up(tok * sizeof(float), 256) + align_up(tok, 256);
+    // adjacent similarities, inverse key norms, run lengths of the anchor rule, flag bytes
+    return 3 * align_up(tok * sizeof(float), 256) + align_up(tok, 256);
 }
 
 }  // namespace kvm
@@ -149,6 +154,8 @@ kvm_status kvm_params_for_budget(double budget, kvm_params *out)
     out->weights = KVM_WEIGHTS_GAUSSIAN;
     out->pivot_rule = KVM_PIVOT_MAX_SCORE;
     out->pivot_seed = 0;
+    out->set_rule = KVM_SETS_ADJACENT;
+    out->reserved = 0;
     return KVM_OK;
 }
 
@@ -201,9 +208,12 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
     }
     const size_t tok = (size_t)shape->B * shape->H_kv * shape->N;
     float *sim = sim_opt ? sim_opt : (float *)ws;
-    uint8_t *flags = (uint8_t *)ws + align_up(tok * sizeof(float), 256);
+    const size_t stride = align_up(tok * sizeof(float), 256);
+    float *inv_norm = (float *)((uint8_t *)ws + stride);
+    int32_t *run = (int32_t *)((uint8_t *)ws + 2 * stride);
+    uint8_t *flags = (uint8_t *)ws + 3 * stride;
     return launch_identify(*shape, *params, capacity(shape, params), K, mass, set_id, set_start, pivot, n_sets, sim,
-                           flags, slice_status, (hipStream_t)stream);
+                           inv_norm, run, flags, slice_status, (hipStream_t)stream);
 }
 
 kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,

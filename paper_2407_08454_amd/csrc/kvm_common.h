@@ -149,7 +149,8 @@ kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, f
                             hipStream_t st);
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,
                            const float *mass, int32_t *set_id, int32_t *set_start, int32_t *pivot,
-                           int32_t *n_sets, float *sim, uint8_t *flags, int32_t *slice_status, hipStream_t st);
+                           int32_t *n_sets, float *sim, float *inv_norm, int32_t *run, uint8_t *flags,
+                           int32_t *slice_status, hipStream_t st);
 kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
                         void *V_out, float *w_opt, int32_t *plan, hipStream_t st);

@@ -104,8 +104,62 @@ def _identify_both(K, mass64, dtype, params, lens=None):
     g = gu.gpu_identify(K, mass32, dtype, params, lens)
     o = ref.identify_sets(K, mass32.astype(np.float64), dtype, params.budget, params.recent_ratio,
                           params.heavy_ratio, params.threshold, bool(params.enforce_budget), g["cap_rows"], lens,
-                          pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed)
+                          pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed, set_rule=params.set_rule)
     return g, o
+
+
+def _compare_anchor_maps(g, o, what):
+    """Anchor rule: one flipped comparison moves every set below it, so a slice is either
+    bit-identical or, when the oracle saw a similarity within NEAR of the threshold, excused."""
+    B, H = o["n_sets"].shape
+    excused = 0
+    for b in range(B):
+        for h in range(H):
+            same = all(np.array_equal(g[k][b, h], o[k][b, h]) for k in ("set_id", "set_start", "pivot")) and \
+                g["n_sets"][b, h] == o["n_sets"][b, h] and g["status"][b, h] == o["status"][b, h]
+            if not same:
+                assert o["anchor_margin"][b, h] <= gu.NEAR, \
+                    f"{what} slice ({b},{h}): maps differ although no comparison came closer than " \
+                    f"{o['anchor_margin'][b, h]:.2e} to the threshold"
+                excused += 1
+    return excused
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_identify_anchor_rule(dtype):
+    n = 1500
+    lens = [n, 1037, 0, 1]
+    _say(f"identify: anchor rule, {dtype}, lens {lens}")
+    Q, K, V = _slices(24, 4, 3, lens, n, 128, 1, dtype)
+    mass = np.random.default_rng(8).random((4, 3, n)) + 0.01
+    total_excused = 0
+    for budget, thr, enforce in ((0.5, 0.75, True), (0.5, 0.5, False), (0.15, 0.9, True), (1.0, -2.0, False)):
+        params = kb.make_params(budget, 0.3 * budget, 0.2 * budget, threshold=thr, enforce_budget=enforce,
+                                set_rule=kb.KVM_SETS_ANCHOR)
+        g, o = _identify_both(K, mass, dtype, params, lens)
+        total_excused += _compare_anchor_maps(g, o, f"anchor {dtype} thr {thr}")
+        gu.check_partition(g, lens, n, g["cap_rows"])
+        np.testing.assert_allclose(g["sim"], o["sim"], atol=2e-6)        # still the adjacent similarities
+        if budget == 0.15:
+            assert (o["status"][0] & kb.KVM_SLICE_INFEASIBLE).all()       # this rule has no fallback
+    _say(f"  excused slices: {total_excused}")
+    assert total_excused <= 4
+
+
+def test_identify_anchor_rule_special_keys():
+    n = 400
+    _say("identify: anchor rule on a turning key, identical keys, zero rows")
+    K = np.zeros((1, 3, n, 128), np.float32)
+    t = np.arange(n)
+    K[0, 0, :, 0], K[0, 0, :, 1] = np.cos(0.1 * t), np.sin(0.1 * t)       # sets of 8 against the anchor
+    K[0, 1] = np.arange(1, 129)                                           # identical keys
+    K[0, 2] = np.random.default_rng(0).standard_normal((n, 128))
+    K[0, 2, 50:60] = 0                                                    # zero-norm keys: similarity 0
+    mass = np.linspace(2, 1, n)[None, None].repeat(3, 1)
+    params = kb.make_params(1.0, 0.0, 0.0, enforce_budget=False, set_rule=kb.KVM_SETS_ANCHOR)
+    g, o = _identify_both(K, mass, "f32", params)
+    assert _compare_anchor_maps(g, o, "anchor special") == 0
+    assert g["n_sets"][0, 0] == 50 and g["n_sets"][0, 1] == 1
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
@@ -413,8 +467,11 @@ def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
         gi = gu.gpu_identify(Ks, m32, dtype, params, ls)
         oi = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
                                params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"], ls,
-                               pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed)
-        gu.compare_maps(gi, oi, ls, N, params.threshold, f"{what} ({b},{h})")
+                               pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed, set_rule=params.set_rule)
+        if params.set_rule == kb.KVM_SETS_ANCHOR:
+            _compare_anchor_maps(gi, oi, f"{what} ({b},{h})")
+        else:
+            gu.compare_maps(gi, oi, ls, N, params.threshold, f"{what} ({b},{h})")
         res = _merge_both(Ks, Vs, dtype, params, oi, ls)
         _check_merge(Ks, Vs, dtype, oi, *res, f"{what} ({b},{h})")
         # end to end: GPU maps from GPU mass against oracle maps from oracle mass
@@ -422,7 +479,7 @@ def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
         if params.pivot_rule == kb.KVM_PIVOT_RANDOM:         # the draws depend on the slice's index in the call
             oe = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
                                    params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"],
-                                   ls, pivot_rule=params.pivot_rule,
+                                   ls, pivot_rule=params.pivot_rule, set_rule=params.set_rule,
                                    pivot_seed=(params.pivot_seed + ((b * H + h) << 32)) % (1 << 64))
         same = all(np.array_equal(g[k][b, h], oe[k][0, 0]) for k in ("set_id", "set_start", "pivot"))
         if same:
@@ -504,7 +561,7 @@ def test_whole_pass_config2_full_size_sampled():
     assert (mass[:, :, 0] >= 1).all() and (mass[:, :, N - 1] <= 1).all() and (mass > 0).all()
 
 
-@pytest.mark.parametrize("variant", ["average_last", "gaussian_random", "fixed_sigma"])
+@pytest.mark.parametrize("variant", ["average_last", "gaussian_random", "fixed_sigma", "anchor_sets"])
 def test_whole_pass_variants(variant):
     """The configurations the paper compares its method with (Section 4.2 first experiment,
     Section 5.4), end to end on two layers of the headline shape."""
@@ -516,7 +573,12 @@ def test_whole_pass_variants(variant):
         params.weights, params.pivot_rule = kb.KVM_WEIGHTS_AVERAGE, kb.KVM_PIVOT_LAST
     elif variant == "gaussian_random":
         params.pivot_rule, params.pivot_seed = kb.KVM_PIVOT_RANDOM, 2024
+    elif variant == "anchor_sets":
+        params.set_rule, params.enforce_budget = kb.KVM_SETS_ANCHOR, 0
     else:
         params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, 5.0
     g = _whole_pass(Q, K, V, "f16", 1, params, lens, [(0, 0), (1, 31)], variant)
-    assert (g["n_sets"] <= cfg["N"] // 2).all()
+    if variant != "anchor_sets":
+        assert (g["n_sets"] <= cfg["N"] // 2).all()
+    else:
+        _say(f"  anchor rule: mean M/n = {g['n_sets'].mean() / cfg['N']:.3f}")

@@ -2,6 +2,7 @@
 average weighted merging and the largest-index pivot (Section 4.2, first experiment), the
 random pivot (Section 5.4, "Choice of Pivotal State").  CPU only."""
 import json
+import math
 import os
 
 import numpy as np
@@ -107,3 +108,109 @@ def test_gaussian_weights_follow_the_chosen_pivot():
     for p, axis in ((0, 0), (5, 1)):
         ko, _, w = ref.merge(K, V, "f32", st, np.array([[[p]]], np.int32), np.array([[1]], np.int32))
         assert w[0, 0, p] == w[0, 0].max() and ko[0, 0, 0, axis] > 0.8 and ko[0, 0, 0, 1 - axis] < 0.5
+
+
+# ---------------------------------------------------------------------------------------------
+# the anchor reading of Algorithm 1: similarity to the set's own top token
+# ---------------------------------------------------------------------------------------------
+
+def _anchor(K, mass, thr=0.75, recent=0.17, heavy=0.12, budget=0.5, enforce=False, lens=None, dtype="f32"):
+    return ref.identify_sets(K, mass, dtype, budget, recent, heavy, thr, enforce, None, lens, set_rule=ref.SETS_ANCHOR)
+
+
+def _restated_anchor_sets(k64, prot, thr):
+    """The same rule from the full cosine matrix (numpy): a set's extent is the trailing run of
+    admissible columns in its anchor's row."""
+    n = len(k64)
+    norm = np.sqrt((k64 * k64).sum(1))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        C = np.where((norm[:, None] > 0) & (norm[None, :] > 0), (k64 @ k64.T) / (norm[:, None] * norm[None, :]), 0.0)
+    starts, i = [], n - 1
+    while i >= 0:
+        s = i
+        if not prot[i]:
+            ok = (C[i, :i] > thr) & ~prot[:i].astype(bool)
+            bad = np.flatnonzero(~ok)
+            s = (bad[-1] + 1) if len(bad) else 0
+        starts.append(s)
+        i = s - 1
+    return starts[::-1]
+
+
+@pytest.mark.parametrize("dtype,seed", [("f32", 0), ("f16", 1), ("bf16", 2)])
+def test_anchor_sets_match_the_matrix_restatement_and_invariants(dtype, seed):
+    n = 700
+    parts = [synth.gen_slice(40 + seed, h, n, 128, 1, None, dtype) for h in range(3)]
+    K = np.stack([p[1] for p in parts])[None]
+    mass = np.random.default_rng(seed).uniform(0.5, 2.0, (1, 3, n))
+    for thr in (0.75, 0.5, 0.9):
+        o = _anchor(K, mass, thr, dtype=dtype)
+        for h in range(3):
+            M = int(o["n_sets"][0, h])
+            want = _restated_anchor_sets(synth.to_f64(K[0, h], dtype), o["protected"][0, h], thr)
+            if o["anchor_margin"][0, h] > 1e-12:             # otherwise a decision sits on the threshold
+                assert o["set_start"][0, h, :M].tolist() == want
+            sid = o["set_id"][0, h]
+            assert sid[0] == 0 and sid[-1] == M - 1 and set(np.diff(sid)) <= {0, 1}
+            prot = np.flatnonzero(o["protected"][0, h])
+            assert len(prot) == math.floor(0.17 * n) + math.floor(0.12 * n)
+            sizes = np.bincount(sid, minlength=M)
+            assert (sizes[sid[prot]] == 1).all()             # conserved tokens are singletons
+            assert ((o["pivot"][0, h, :M] >= o["set_start"][0, h, :M])).all()
+
+
+def test_anchor_sets_on_a_slowly_turning_key():
+    # keys on a circle, turning by theta per token: neighbours always pass the threshold, so the
+    # adjacent chain gives one set; against the anchor only floor(acos(eps)/theta) tokens do
+    n, theta, eps = 100, 0.1, 0.75
+    t = np.arange(n)
+    K = np.zeros((1, 1, n, 128), np.float32)
+    K[0, 0, :, 0], K[0, 0, :, 1] = np.cos(theta * t), np.sin(theta * t)
+    mass = np.ones((1, 1, n))
+    kw = dict(recent=0.0, heavy=0.0, budget=1.0)
+    chain = ref.identify_sets(K, mass, "f32", 1.0, 0.0, 0.0, eps, False, None)
+    assert chain["n_sets"][0, 0] == 1
+    o = _anchor(K, mass, eps, **kw)
+    per_set = math.floor(math.acos(eps) / theta) + 1         # the anchor and the tokens within the angle
+    assert per_set == 8
+    M = math.ceil(n / per_set)
+    assert o["n_sets"][0, 0] == M
+    # sets are cut from the last token downwards; the first set takes what is left
+    assert o["set_start"][0, 0, :M].tolist() == [0] + list(range(n - per_set * (M - 1), n, per_set))
+
+
+def test_anchor_special_cases():
+    n = 64
+    rng = np.random.default_rng(3)
+    mass = rng.uniform(1, 2, (1, 1, n))
+    K = np.tile(rng.standard_normal(128).astype(np.float32), (1, 1, n, 1))
+    o = _anchor(K, mass, 0.75, recent=0.1, heavy=0.1)        # identical keys: one set per free stretch
+    free = ~o["protected"][0, 0].astype(bool)
+    stretches = int(np.sum(free & ~np.concatenate([[False], free[:-1]])))
+    assert o["n_sets"][0, 0] == stretches + int((~free).sum())
+    K = np.zeros((1, 1, n, 128), np.float32)
+    K[0, 0, np.arange(n), np.arange(n)] = 1.0                # orthogonal keys: all singletons
+    assert _anchor(K, mass, 0.75)["n_sets"][0, 0] == n
+    K = rng.standard_normal((1, 1, n, 128)).astype(np.float32)
+    assert _anchor(K, mass, 1.0, recent=0, heavy=0)["n_sets"][0, 0] == n          # nothing exceeds 1
+    assert _anchor(K, mass, -1.5, recent=0, heavy=0)["n_sets"][0, 0] == 1         # everything exceeds -1.5
+    # strictness: similarity exactly at the threshold does not join
+    K = np.zeros((1, 1, 3, 128), np.float32)
+    K[0, 0, :, 0] = [1, 1, 1]
+    K[0, 0, 0, 1] = 1.0                                      # cos(k2, k0) = cos(k1, k0) = 1/sqrt(2)
+    c = float(np.float64(1.0) / np.sqrt(np.float64(2.0)))
+    m3 = np.ones((1, 1, 3))
+    assert _anchor(K, m3, c, recent=0, heavy=0)["set_start"][0, 0, :2].tolist() == [0, 1]
+    assert _anchor(K, m3, np.nextafter(c, 0), recent=0, heavy=0)["n_sets"][0, 0] == 1
+
+
+def test_anchor_rule_reports_a_missed_budget_and_truncates():
+    n = 300
+    parts = synth.gen_slice(50, 0, n, 128, 1, None, "f32")
+    K = parts[1][None, None]
+    mass = np.random.default_rng(4).uniform(1, 2, (1, 1, n))
+    o = ref.identify_sets(K, mass, "f32", 0.2, 0.1, 0.05, 0.95, True, 60, None, set_rule=ref.SETS_ANCHOR)
+    M = int(o["n_sets"][0, 0])
+    assert M > 60 and o["status"][0, 0] == (ref.SLICE_INFEASIBLE | ref.SLICE_TRUNCATED)
+    free = _anchor(K, mass, 0.95, recent=0.1, heavy=0.05)
+    assert np.array_equal(free["set_start"][0, 0, :61], o["set_start"][0, 0])     # no fallback: same sets, cut off
