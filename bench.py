@@ -58,8 +58,8 @@ def main() -> int:
                     help="also run one plain device copy of K before the timed region (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (slices are independent; see DESIGN.md for how it "
-              "would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (every (layer, head) slice is independent, so more GPUs "
+              "would each take a share of the slices with no exchange); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -199,7 +199,11 @@ def main() -> int:
         "config": {"workload": f"configs[{args.config - 1}] {cfg['name']}: {B // cfg['batch']} layers x {H} KV heads, "
                                f"G={G}, N={N}, d={d}, {dtype}, budget {args.budget}, AR(1) keys seed {cfg['seed']}; {variant}",
                    "slices": B * H, "token_slices_per_step": token_slices, "merged_rows_per_step": M_total,
-                   "mean_M_over_n": M_total / token_slices, "slices_with_fallback": int((status != 0).sum())},
+                   "mean_M_over_n": M_total / token_slices, "slices_with_fallback": int((status != 0).sum()),
+                   # merged length over original length per layer (the layer-wise compression ratio of Section 3.2)
+                   "M_over_n_per_layer": [round(float(x), 4) for x in
+                                          (n_sets.reshape(-1, cfg["batch"], H).sum((1, 2)) /
+                                           (n_per_b.reshape(-1, cfg["batch"]).sum(1) * H))]},
         "roofline": roofline, "cpu_baseline": cpu,
         "stage_ms": {"attn_mass": stage_ms[0] / args.steps, "identify_sets": stage_ms[1] / args.steps,
                      "merge": stage_ms[2] / args.steps},

@@ -247,10 +247,20 @@ __device__ __forceinline__ f32x16 score_block(const u32x4 *tile, int blk, const 
 
 // Unmasked tiles (16-bit types): the 8 A fragments of a 32-row block are fetched once, all
 // reads in flight together, and serve both stationary blocks of the wave.
+// The slot of fragment f of a lane within a 32-row block does not depend on the block or the
+// stage; the eight slots are computed once and the block and stage become constant offsets.
+struct FragSlots { int v[8]; };
 template <typename T>
-__device__ __forceinline__ void load_frags8(const u32x4 *tile, int blk, int lane, u32x4 *a) {
+__device__ __forceinline__ FragSlots frag_slots(int lane) {
+    FragSlots s;
 #pragma unroll
-    for (int f = 0; f < 8; ++f) a[f] = Tile<T>::frag(tile, blk, f, lane);
+    for (int f = 0; f < 8; ++f) s.v[f] = Tile<T>::lds_index(lane & 31, 2 * f + (lane >> 5));
+    return s;
+}
+template <typename T>
+__device__ __forceinline__ void load_frags8(const u32x4 *tile, int blk, const FragSlots &s, u32x4 *a) {
+#pragma unroll
+    for (int f = 0; f < 8; ++f) a[f] = tile[s.v[f] + 32 * Tile<T>::CH * blk];
 }
 
 template <typename T>
@@ -304,6 +314,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     const T *Qs = Q + (size_t)qslice * N * HEAD_DIM;
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
     const typename TL::Offsets off = TL::offsets(wave, lane);
+    const FragSlots fs = frag_slots<T>(lane);
 
     // Workgroup t of a slice takes row tile tiles-1-t, the one with the longest rows left; with
     // fewer workgroups than tiles it then also takes tile t, the shortest left, so that all
@@ -347,12 +358,12 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
             // not fit the register budget
             if (s < diag) {                                   // four full blocks
                 u32x4 a[8];
-                load_frags8<T>(cur, 0, lane, a);
+                load_frags8<T>(cur, 0, fs, a);
                 f32x16 acc = score_block8<T>(a, qf[0]);
                 rowstat_update(acc, c, m_run[0], l_run[0]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, qf[1]);
-                load_frags8<T>(cur, 1, lane, a);              // in flight during the reduction below
+                load_frags8<T>(cur, 1, fs, a);              // in flight during the reduction below
                 rowstat_update(acc, c, m_run[1], l_run[1]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, qf[0]);
@@ -362,13 +373,13 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
                 rowstat_update(acc, c, m_run[1], l_run[1]);
             } else if (s == diag) {                           // two blocks on the diagonal, one below it
                 u32x4 a[8];
-                load_frags8<T>(cur, 0, lane, a);              // keys q0 .. q0+31
+                load_frags8<T>(cur, 0, fs, a);              // keys q0 .. q0+31
                 f32x16 acc = score_block8<T>(a, qf[0]);
                 mask_rows_above_col(acc, lane);               // accumulator rows are keys, columns queries
                 rowstat_update(acc, c, m_run[0], l_run[0]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, qf[1]);
-                load_frags8<T>(cur, 1, lane, a);              // keys q0+32 .. q0+63
+                load_frags8<T>(cur, 1, fs, a);              // keys q0+32 .. q0+63
                 rowstat_update(acc, c, m_run[1], l_run[1]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, qf[1]);
@@ -457,6 +468,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     const int last = (n - 1) / TR;
     const int steps = (last - first + 1) * G;
     const typename TL::Offsets off = TL::offsets(wave, lane);
+    const FragSlots fs = frag_slots<T>(lane);
     auto issue = [&](int g, int qt, u32x4 *stage, float *stage_lse) {   // Q rows and their statistics -> LDS
         const size_t qslice = ((size_t)b * H + h) * G + g;
         const T *Qh = Q + qslice * N * HEAD_DIM;
@@ -494,13 +506,13 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
             // not fit the register budget
             if (qt > diag) {                                  // four full blocks
                 u32x4 a[8];
-                load_frags8<T>(cur, 0, lane, a);
+                load_frags8<T>(cur, 0, fs, a);
                 RowStats L = load_rowstats(cur_lse, 0, lane);
                 f32x16 acc = score_block8<T>(a, kf[0]);
                 colsum_update(acc, L, c, part[0]);
                 __builtin_amdgcn_sched_barrier(0);
                 acc = score_block8<T>(a, kf[1]);
-                load_frags8<T>(cur, 1, lane, a);              // in flight during the reduction below
+                load_frags8<T>(cur, 1, fs, a);              // in flight during the reduction below
                 colsum_update(acc, L, c, part[1]);
                 __builtin_amdgcn_sched_barrier(0);
                 L = load_rowstats(cur_lse, 1, lane);
@@ -511,10 +523,10 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
                 colsum_update(acc, L, c, part[1]);
             } else if (qt == diag) {                          // two blocks on the diagonal, one below it
                 u32x4 a[8];
-                load_frags8<T>(cur, 0, lane, a);              // queries k0 .. k0+31
+                load_frags8<T>(cur, 0, fs, a);              // queries k0 .. k0+31
                 RowStats L = load_rowstats(cur_lse, 0, lane);
                 f32x16 acc = score_block8<T>(a, kf[0]);
-                load_frags8<T>(cur, 1, lane, a);              // queries k0+32 .. k0+63
+                load_frags8<T>(cur, 1, fs, a);              // queries k0+32 .. k0+63
                 mask_rows_below_col(acc, lane);               // accumulator rows are queries, columns keys
                 colsum_update(acc, L, c, part[0]);
                 __builtin_amdgcn_sched_barrier(0);
