@@ -205,6 +205,19 @@ __device__ __forceinline__ void rowstat_update(const f32x16 &acc, float c, float
     m_run = m_new;
 }
 
+// pass 1 with the reference held: 16 more terms exp2(c s - mc) of a row's sum, no maximum and
+// no rescaling.  Any reference gives the same log-sum-exp as long as no term overflows; the
+// caller checks the finished sums for that.
+__device__ __forceinline__ void rowsum_held(const f32x16 &acc, float c, float mc, float &l_run) {
+    float p0 = __builtin_amdgcn_exp2f(fmaf(acc[0], c, -mc)), p1 = __builtin_amdgcn_exp2f(fmaf(acc[1], c, -mc));
+#pragma unroll
+    for (int i = 2; i < 16; i += 2) {
+        p0 += __builtin_amdgcn_exp2f(fmaf(acc[i], c, -mc));
+        p1 += __builtin_amdgcn_exp2f(fmaf(acc[i + 1], c, -mc));
+    }
+    l_run += p0 + p1;
+}
+
 // pass 2: the row statistics L of a 32-row block of the streamed tile, in the order of a
 // lane's accumulators (accumulator i of lane l is row 8*(i/4) + 4*(l/32) + i%4)
 struct RowStats { f32x4 v[4]; };
@@ -289,9 +302,16 @@ __device__ __forceinline__ void mask_rows_below_col(f32x16 &acc, int lane) {
         if (acc_row(i, lane) < (lane & 31)) acc[i] = -INFINITY;
 }
 
-template <typename T>
+// HOLD (16-bit types only): the running maximum is taken from key tile 0 and held for the tiles
+// below the diagonal, which saves the maximum and the rescaling of every block; the diagonal
+// tile updates it again.  Should a later score exceed the held maximum by so much that a term
+// overflows, the sums are not finite: the workgroup then records the row tile in `redo`, and a
+// second launch without HOLD, which looks only at recorded tiles, computes it with the maximum
+// updated at every block.  Without HOLD and with redo == NULL every tile is computed.
+template <typename T, bool HOLD>
 __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(const T *__restrict__ Q, const T *__restrict__ K,
-                                                                 float *__restrict__ lse, const int32_t *__restrict__ seq_lens,
+                                                                 float *__restrict__ lse, int32_t *__restrict__ redo,
+                                                                 const int32_t *__restrict__ seq_lens,
                                                                  int n_qslices, int HG, int G, int N, int n_pad,
                                                                  int tiles_per_slice, int wgs_per_slice, float c)
 {
@@ -325,6 +345,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     if (pass == 1 && (!paired || tm.tile >= tiles_per_slice - 1 - tm.tile)) break;
     const int q_begin = tile * ROWS_PER_BLOCK;
     if (q_begin >= n) continue;
+    if (!HOLD && redo && !redo[(size_t)qslice * tiles_per_slice + tile]) continue;
     const int q0 = q_begin + wave * 32 * NB;                  // first query row of this wave
 
     const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
@@ -332,13 +353,13 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     auto issue = [&](int t, u32x4 *stage) {                   // key tile t on its way into LDS
         TL::issue(Ks, t * TR, n, off, stage, wave, lane);
     };
-    issue(0, lds_a);
 
     u32x4 qf[NB][M::FRAGS];
 #pragma unroll
     for (int qb = 0; qb < NB; ++qb) load_stationary<T>(Qs, q0 + 32 * qb, n, lane, qf[qb]);
 
     float m_run[NB], l_run[NB];
+    issue(0, lds_a);
 #pragma unroll
     for (int qb = 0; qb < NB; ++qb) { m_run[qb] = M_INIT; l_run[qb] = 0.f; }
 
@@ -356,7 +377,23 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
         if constexpr (NB == 2) {
             // the fences keep the scheduler from hoisting later blocks' LDS reads, which would
             // not fit the register budget
-            if (s < diag) {                                   // four full blocks
+            if (HOLD && s < diag && s > 0) {                  // four full blocks, maximum held
+                const float mc0 = m_run[0] * c, mc1 = m_run[1] * c;
+                u32x4 a[8];
+                load_frags8<T>(cur, 0, fs, a);
+                f32x16 acc = score_block8<T>(a, qf[0]);
+                rowsum_held(acc, c, mc0, l_run[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[1]);
+                load_frags8<T>(cur, 1, fs, a);              // in flight during the reduction below
+                rowsum_held(acc, c, mc1, l_run[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[0]);
+                rowsum_held(acc, c, mc0, l_run[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                acc = score_block8<T>(a, qf[1]);
+                rowsum_held(acc, c, mc1, l_run[1]);
+            } else if (s < diag) {                            // four full blocks
                 u32x4 a[8];
                 load_frags8<T>(cur, 0, fs, a);
                 f32x16 acc = score_block8<T>(a, qf[0]);
@@ -413,6 +450,13 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
         if (s + 1 < steps) step(s + 1, lds_b, lds_a);
     }
     wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
+    if constexpr (HOLD) {
+        bool finite = true;
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) finite = finite && l_run[qb] <= 3.0e38f;   // false for +inf and NaN
+        const int bad = __syncthreads_or(finite ? 0 : 1);
+        if (threadIdx.x == 0) redo[(size_t)qslice * tiles_per_slice + tile] = bad;
+    }
     // lanes l and l+32 hold the two halves of a row's keys; rows in [n, n_pad) get +inf so
     // that the second pass weighs them with exp2(-inf) = 0
 #pragma unroll
@@ -595,9 +639,24 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
         // which nothing overlaps, costs more than the even load gains)
         const int wgs = tiles >= 8 ? (tiles + 1) / 2 : tiles;
         const long long blocks = (long long)((n_q + 7) / 8) * 8 * wgs;
-        ProfScope prof("attn_lse_kernel", st);
-        hipLaunchKernelGGL(attn_lse_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q, (const T *)K,
-                           lse, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c);
+        int32_t *redo = reinterpret_cast<int32_t *>(lse + (size_t)n_q * n_pad);   // one flag per (query slice, row tile)
+        if constexpr (Mma<T>::NBLK == 2) {
+            {
+                ProfScope prof("attn_lse_kernel", st);
+                hipLaunchKernelGGL((attn_lse_kernel<T, true>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
+                                   (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c);
+            }
+            kvm_status rc = check_launch("attn_lse_kernel");
+            if (rc != KVM_OK) return rc;
+            ProfScope prof("attn_lse_redo_kernel", st);
+            hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
+                               (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c);
+        } else {
+            ProfScope prof("attn_lse_kernel", st);
+            hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
+                               (const T *)K, lse, (int32_t *)nullptr, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad,
+                               tiles, wgs, c);
+        }
         kvm_status rc = check_launch("attn_lse_kernel");
         if (rc != KVM_OK) return rc;
     }
@@ -612,6 +671,8 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
 
 // Row statistics are stored with the sequence length rounded up to a whole streamed tile.
 int attn_lse_stride(int N) { return (N + 63) / 64 * 64; }
+// Row tiles per slice, for the flags that follow the row statistics in the workspace.
+int attn_row_tiles(int N) { return (N + 255) / 256; }
 
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse, hipStream_t st)
 {

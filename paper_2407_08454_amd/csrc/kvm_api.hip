@@ -120,7 +120,9 @@ static int capacity(const kvm_shape *sh, const kvm_params *pr)
 
 static size_t ws_attn(const kvm_shape *sh)
 {
-    return align_up((size_t)sh->B * sh->H_kv * sh->G * attn_lse_stride(sh->N) * sizeof(float), 256);
+    // row statistics, then one flag per (query slice, row tile)
+    const size_t q_slices = (size_t)sh->B * sh->H_kv * sh->G;
+    return align_up(q_slices * attn_lse_stride(sh->N) * sizeof(float) + q_slices * attn_row_tiles(sh->N) * sizeof(int32_t), 256);
 }
 static size_t ws_identify(const kvm_shape *sh)
 {

@@ -156,5 +156,6 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
                         void *V_out, float *w_opt, int32_t *plan, hipStream_t st);
 size_t merge_workspace_bytes(const kvm_shape &sh);
 int attn_lse_stride(int N);
+int attn_row_tiles(int N);
 
 }  // namespace kvm

@@ -80,6 +80,34 @@ def test_mass_config1_and_determinism():
     assert np.array_equal(got, gu.gpu_mass(Q, K, "f32"))          # no atomics: bitwise repeatable
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_mass_scores_rising_far_above_the_first_keys(dtype):
+    """Scores that grow by hundreds along the sequence: a softmax reference taken from the first
+    keys cannot be held (the exponentials overflow), so the row statistics have to come out of
+    the path that updates the maximum at every block."""
+    n = 700
+    _say(f"mass: rising scores, {dtype}")
+    rng = np.random.default_rng(12)
+    q = rng.standard_normal((1, 2, n, 128)).astype(np.float32)
+    k = rng.standard_normal((1, 2, n, 128)).astype(np.float32)
+    # head 0: every query and key shares a component that grows with the position
+    ramp = np.linspace(0.0, 60.0, n, dtype=np.float32)
+    q[0, 0, :, 0] = 40.0
+    k[0, 0, :, 0] = ramp
+    # head 1: a single late key far above everything before it
+    q[0, 1, :, 1] = 30.0
+    k[0, 1, 400, 1] = 90.0
+    Q, K = synth.to_storage(q, dtype), synth.to_storage(k, dtype)
+    want = ref.attn_mass(Q, K, dtype)
+    got = gu.gpu_mass(Q, K, dtype)
+    assert np.isfinite(got).all()
+    # the mass sits on few keys here; compare where the oracle's mass is not negligible and
+    # require the rest to be small
+    big = want > 1e-6
+    assert (np.abs(got[big] - want[big]) / want[big]).max() <= gu.TOL
+    assert np.abs(got[~big]).max() <= 2e-6 and got.sum() == pytest.approx(2 * n, rel=1e-4)
+
+
 def test_mass_large_scores_do_not_overflow():
     # keys and queries scaled so that raw scores reach the hundreds: the row maximum must be used
     n = 200
