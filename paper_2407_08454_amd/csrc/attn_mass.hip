@@ -479,7 +479,8 @@ template <typename T>
 __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const float *__restrict__ lse, float *__restrict__ mass,
                                                                     const int32_t *__restrict__ seq_lens, int n_kvslices,
-                                                                    int H, int G, int N, int n_pad, int tiles_per_slice, float c)
+                                                                    int H, int G, int N, int n_pad, int tiles_per_slice,
+                                                                    int wgs_per_slice, float c)
 {
     using M = Mma<T>;
     using TL = Tile<T>;
@@ -489,21 +490,29 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     __shared__ u32x4 lds_a[TL::SLOTS], lds_b[TL::SLOTS];
     __shared__ __attribute__((aligned(16))) float lse_a[64], lse_b[64];
 
-    const TileMap tm = map_block(n_kvslices, tiles_per_slice);
+    const TileMap tm = map_block(n_kvslices, wgs_per_slice);
     if (!tm.valid) return;
-    const int kvslice = tm.slice, tile = tm.tile;             // tile 0 has the most rows below it
+    const int kvslice = tm.slice;
     const int b = kvslice / H, h = kvslice % H;
     const int n = clamp_len(seq_lens, b, N);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar: per-wave branches stay scalar
+    float *mass_s = mass + (size_t)kvslice * N;
+    const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
+    const typename TL::Offsets off = TL::offsets(wave, lane);
+    const FragSlots fs = frag_slots<T>(lane);
+    // workgroup t takes key tile t (tile 0 has the most rows below it) and, when there are fewer
+    // workgroups than tiles, then also tile tiles-1-t (see attn_lse_kernel)
+    const bool paired = wgs_per_slice < tiles_per_slice;
+    for (int pass = 0; pass < 2; ++pass) {
+    const int tile = pass == 0 ? tm.tile : tiles_per_slice - 1 - tm.tile;
+    if (pass == 1 && (!paired || tm.tile >= tiles_per_slice - 1 - tm.tile)) break;
     const int k_begin = tile * KEYS_PER_BLOCK;
     const int k0 = k_begin + wave * 32 * NB;
-    float *mass_s = mass + (size_t)kvslice * N;
     if (k_begin >= n) {                                       // padding only: defined zeros
         for (int j = k_begin + threadIdx.x; j < min(k_begin + KEYS_PER_BLOCK, N); j += ATT_BLOCK) mass_s[j] = 0.f;
-        return;
+        continue;
     }
-    const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
 
     // Query tiles first .. last see these keys.  They are streamed from the last one down, head
     // after head: every workgroup of a slice then starts at the same tile and walks down in step
@@ -511,8 +520,6 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     const int first = k_begin / TR;
     const int last = (n - 1) / TR;
     const int steps = (last - first + 1) * G;
-    const typename TL::Offsets off = TL::offsets(wave, lane);
-    const FragSlots fs = frag_slots<T>(lane);
     auto issue = [&](int g, int qt, u32x4 *stage, float *stage_lse) {   // Q rows and their statistics -> LDS
         const size_t qslice = ((size_t)b * H + h) * G + g;
         const T *Qh = Q + qslice * N * HEAD_DIM;
@@ -617,6 +624,8 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
         const int key = k0 + 32 * kb + (lane & 31);
         if (lane < 32 && key < N) mass_s[key] = key < n ? total : 0.f;
     }
+    barrier_no_fence();                                       // everybody is done with LDS before the next tile's loads
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -661,10 +670,11 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
         if (rc != KVM_OK) return rc;
     }
     {
-        const long long blocks = (long long)((n_kv + 7) / 8) * 8 * tiles;
+        const int wgs = tiles >= 8 ? (tiles + 1) / 2 : tiles;   // as for the row statistics
+        const long long blocks = (long long)((n_kv + 7) / 8) * 8 * wgs;
         ProfScope prof("attn_colsum_kernel", st);
         hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
-                           (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, c);
+                           (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, wgs, c);
         return check_launch("attn_colsum_kernel");
     }
 }
