@@ -34,6 +34,8 @@ def test_presets_follow_the_printed_hyperparameters():
     p = kb.kvm_params_for_budget(0.35)
     assert (p.budget, p.recent_ratio, p.heavy_ratio, p.threshold) == (0.35, 0.08, 0.02, 0.75)
     assert p.enforce_budget == 1 and p.value_scale_by_set_size == 1 and p.sigma_mode == kb.KVM_SIGMA_MEAN_DIST
+    assert (p.weights, p.pivot_rule, p.pivot_seed, p.set_rule) == (kb.KVM_WEIGHTS_GAUSSIAN, kb.KVM_PIVOT_MAX_SCORE, 0,
+                                                                   kb.KVM_SETS_ADJACENT)
     p = kb.kvm_params_for_budget(0.25)
     assert p.recent_ratio + p.heavy_ratio < 0.25
     with pytest.raises(kb.KvmError):
@@ -55,7 +57,7 @@ def test_capacity_and_workspace():
     assert kb.kvm_out_capacity(_shape(N=4096), p) == 4096
     sh = _shape(B=4, H_kv=8, G=4, N=1000)
     need = kb.kvm_workspace_bytes(sh, p)
-    assert need >= 4 * 8 * 4 * 1000 * 4 and need >= 4 * 8 * 1000 * 5
+    assert need >= 4 * 8 * 4 * 1000 * 4 and need >= 4 * 8 * 1000 * 13
     assert kb.kvm_workspace_bytes(_shape(d=64), p) == 0
 
 
@@ -85,6 +87,10 @@ def test_host_detectable_errors_return_before_any_launch():
     assert ident(_shape(), kb.make_params(1.5, 0.1, 0.1)) == kb.KVM_ERR_INVALID_ARG
     assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, threshold=float("nan"))) == kb.KVM_ERR_INVALID_ARG
     assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, sigma_mode=5)) == kb.KVM_ERR_UNSUPPORTED
+    assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, weights=2)) == kb.KVM_ERR_UNSUPPORTED
+    assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, pivot_rule=3)) == kb.KVM_ERR_UNSUPPORTED
+    assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, set_rule=2)) == kb.KVM_ERR_UNSUPPORTED and \
+        b"set_rule" in lib.kvm_last_error()
     assert ident(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
     assert ident(_shape(), p, nbytes=8) == kb.KVM_ERR_WORKSPACE
 
