@@ -610,3 +610,27 @@ def test_whole_pass_variants(variant):
         assert (g["n_sets"] <= cfg["N"] // 2).all()
     else:
         _say(f"  anchor rule: mean M/n = {g['n_sets'].mean() / cfg['N']:.3f}")
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_whole_pass_random_shapes(case):
+    """Seeded random shapes, lengths, group sizes, types, budgets and variants: every slice of a
+    small batch goes through the oracle."""
+    rng = np.random.default_rng(1000 + case)
+    dtype = ["f16", "bf16", "f32"][case % 3]
+    B, H, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4]))
+    N = int(rng.choice([1, 63, 64, 65, 255, 256, 257, 511, 513, 700, 1025, 1300]))
+    lens = [int(x) for x in rng.integers(0, N + 1, B)]
+    lens[int(rng.integers(0, B))] = N                        # one sequence at full length
+    budget = float(rng.choice([0.35, 0.5, 0.8]))
+    params = kb.kvm_params_for_budget(budget)
+    params.weights = int(rng.choice([kb.KVM_WEIGHTS_GAUSSIAN, kb.KVM_WEIGHTS_AVERAGE]))
+    params.pivot_rule = int(rng.choice([kb.KVM_PIVOT_MAX_SCORE, kb.KVM_PIVOT_LAST, kb.KVM_PIVOT_RANDOM]))
+    params.pivot_seed = int(rng.integers(0, 1 << 40))
+    params.set_rule = int(rng.choice([kb.KVM_SETS_ADJACENT, kb.KVM_SETS_ANCHOR]))
+    params.threshold = float(rng.choice([0.6, 0.75, 0.9]))
+    _say(f"random shapes {case}: {dtype} B={B} H={H} G={G} N={N} lens={lens} budget={budget} "
+         f"weights={params.weights} pivot={params.pivot_rule} sets={params.set_rule} eps={params.threshold}")
+    Q, K, V = _slices(2000 + case, B, H, lens, N, 128, G, dtype)
+    sample = [(b, h) for b in range(B) for h in range(H)]
+    _whole_pass(Q, K, V, dtype, G, params, lens, sample, f"random shapes {case}")
