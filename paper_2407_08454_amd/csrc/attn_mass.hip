@@ -12,9 +12,14 @@
 //                       accumulators all belong to one column, so the column sum needs no
 //                       cross-lane traffic until the very end and no atomics: deterministic.
 // The operand that sits in registers is the MFMA B operand in both kernels; the streamed
-// tile is the A operand.  Tiles go from global memory straight into a ring of LDS stages
-// (global_load_lds, no registers in between), several tiles ahead of the one being used,
-// with an XOR swizzle of their 16-byte chunks so that the fragment reads are conflict-free.
+// tile is the A operand.  Tiles go from global memory straight into one of two LDS stages
+// (global_load_lds, no registers in between), one tile ahead of the one being used, with an
+// XOR swizzle of their 16-byte chunks so that the fragment reads are conflict-free.
+//
+// On this chip the pair (one MFMA block, its softmax arithmetic) is bound by VALU issue slots
+// and by power, not by the matrix pipe: at d = 128 a 32x32 block costs 8 MFMAs (256 cycles) and
+// at least 48 VALU instructions (one fma, one exp2, one add per score), and packed fp32
+// arithmetic is not used.  Hence the attention to every VALU instruction in the block loops.
 #include "kvm_common.h"
 
 namespace kvm {
@@ -174,10 +179,10 @@ __device__ __forceinline__ TileMap map_block(int n_slices, int tiles_per_slice) 
 // per-block reductions
 //
 // A wave issues at most one instruction every other issue slot of its SIMD, so the vector
-// ALU and the matrix pipe only stay busy with about four waves per SIMD.  The kernels are
-// therefore written to fit 128 registers (64 of them hold the stationary operand): one
-// accumulator block at a time, fragments fetched four at a time, and the overlap of MFMA,
-// exp2 and LDS traffic is left to the hardware interleaving the waves.
+// ALU and the matrix pipe only stay busy with several waves per SIMD.  The kernels are
+// written to fit three waves per SIMD (168 registers, 64 of them for the stationary operand):
+// one accumulator block at a time, the eight fragments of a block fetched together, and the
+// overlap of MFMA, exp2 and LDS traffic is left to the hardware interleaving the waves.
 // ------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ float max16(const f32x16 &v) {
