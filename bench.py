@@ -49,6 +49,8 @@ def main() -> int:
                     help="merge weights (average = the average weighted merging of Section 4.2)")
     ap.add_argument("--pivot", choices=["max-score", "last", "random"], default="max-score",
                     help="pivot rule (last = largest index, Section 4.2; random = Section 5.4)")
+    ap.add_argument("--method", choices=["merge", "evict"], default="merge",
+                    help="evict = the comparison workload: attention mass, then plain eviction by score (kvm_evict)")
     ap.add_argument("--sets", choices=["adjacent", "anchor"], default="adjacent",
                     help="reading of Algorithm 1 (anchor = similarity to the set's top token; no budget fallback)")
     ap.add_argument("--sigma", type=float, default=None, help="fixed sigma (Section 5.4) instead of the per-set one")
@@ -99,8 +101,19 @@ def main() -> int:
     shape = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(shape, params, "cuda", tdt)
 
+    evict = args.method == "evict"
+    if evict:
+        variant = "comparison workload: eviction by score"
+        # kept positions go where the pivots would, their count where the set count would
+        def rest():
+            kb.kvm_evict(shape, params, Kd, Vd, buf.mass, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.ws)
+        buf.status.zero_()
     for _ in range(args.warmup):
-        kb.compress(shape, params, Qd, Kd, Vd, buf)
+        if evict:
+            kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+            rest()
+        else:
+            kb.compress(shape, params, Qd, Kd, Vd, buf)
     torch.cuda.synchronize()
     if args.calibration_copy:          # reads and writes K.numel() * element_size bytes exactly once
         copy = torch.empty_like(Kd)
@@ -117,10 +130,15 @@ def main() -> int:
         e[0].record()
         kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
         e[1].record()
-        kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, None,
-                             buf.status, buf.ws)
-        e[2].record()
-        kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None, buf.ws)
+        if evict:
+            e[2].record()
+            rest()
+        else:
+            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, None,
+                                 buf.status, buf.ws)
+            e[2].record()
+            kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None,
+                         buf.ws)
         e[3].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -144,7 +162,7 @@ def main() -> int:
     roofline = None
     hbm = {}
     headline = (args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
-                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent")
+                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and not evict)
 
     def traffic(name):
         return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None
@@ -170,7 +188,9 @@ def main() -> int:
 
     # ---- the oracle on the host cores, on a sample of the same slices --------------------------
     cpu = None
-    if args.cpu_slices > 0:
+    if args.cpu_slices > 0 and evict:
+        print("bench.py: no CPU baseline leg for --method evict (use --cpu-slices 0)", file=sys.stderr)
+    if args.cpu_slices > 0 and not evict:
         from oracle import ref
         S = min(args.cpu_slices, B * H)
         idx = np.linspace(0, B * H - 1, S).astype(int)          # spread over layers and heads

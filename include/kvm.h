@@ -7,6 +7,7 @@
  *   kvm_attn_mass      aggregated attention score of every key
  *   kvm_identify_sets  contiguous merging sets + pivot of each set
  *   kvm_merge          Gaussian-kernel weighted merge into a compacted cache
+ * (kvm_evict is a comparison workload: plain eviction by the same scores)
  *
  * Conventions for every call
  *   - Every tensor pointer is a DEVICE pointer to contiguous memory, innermost
@@ -221,6 +222,26 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
 kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
                      const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,
                      void *K_out, void *V_out, float *w_opt, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Comparison workload, not part of the method: eviction by aggregated attention score, the
+ * selection policy of the heavy-hitter methods the paper measures itself against (Section 2.3;
+ * Section 4.2 compares average weighted merging with it at the same budget).  Per slice it
+ * keeps floor(budget n) tokens: the last floor(recent_ratio n) and those with the largest
+ * `mass` among the others (ties: lower index), and gathers their rows in sequence order.
+ * Nothing is merged.  params is validated as for the other calls; its heavy_ratio, threshold
+ * and merge fields are not used.
+ *   K, V     in   (B, H_kv, N, d)
+ *   mass     in   (B, H_kv, N) float32
+ *   kept     out  (B, H_kv, capacity) int32: kept positions, ascending; -1 beyond n_kept
+ *   n_kept   out  (B, H_kv) int32
+ *   K_out, V_out  out  (B, H_kv, capacity, d): row s = row kept[s] of K / V, bit for bit;
+ *            rows >= n_kept are not written
+ * capacity = kvm_out_capacity(); ws as for kvm_identify_sets.
+ */
+kvm_status kvm_evict(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                     const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out,
+                     void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Per-kernel timing for benchmarks (not part of the method; no citation).  While

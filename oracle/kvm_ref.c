@@ -475,6 +475,56 @@ int kvm_ref_merge(int B, int H, int N, int d, int dtype, const int32_t *seq_lens
     return 0;
 }
 
+/* ========================================================================= */
+/* comparison workload: eviction by aggregated attention score                 */
+/* ========================================================================= */
+
+/*
+ * The selection policy of the heavy-hitter eviction methods the paper compares with
+ * (Section 2.3): per slice keep floor(budget n) tokens -- the last floor(recent_ratio n)
+ * (cut to the budget if wider) and the largest scores among the others (ties: lower
+ * index) -- and drop the rest.  kept: (B, H, cap_rows) ascending positions, -1 beyond
+ * n_kept; K_out, V_out: (B, H, cap_rows, d) fp64 copies of the kept rows.
+ */
+int kvm_ref_evict(int B, int H, int N, int d, int dtype, const int32_t *seq_lens, double budget,
+                  double recent_ratio, int cap_rows, const void *K, const void *V, const double *mass,
+                  int32_t *kept, int32_t *n_kept, double *K_out, double *V_out)
+{
+    int bh;
+    if (B < 0 || H < 1 || N < 0 || d < 1 || cap_rows < 0 || !n_kept) return 1;
+    for (bh = 0; bh < B * H; ++bh) {
+        int b = bh / H;
+        int n = valid_len(seq_lens, b, N);
+        int cap = (int)floor(budget * (double)n);
+        int n_recent = (int)floor(recent_ratio * (double)n);
+        int pre, k, j, m = 0;
+        unsigned char *keep = (unsigned char *)calloc((size_t)n + 1, 1);
+        ranked *rk = (ranked *)malloc(sizeof(ranked) * (size_t)(n + 1));
+        double *row = (double *)malloc(sizeof(double) * (size_t)d);
+        if (cap > cap_rows) cap = cap_rows;
+        if (n_recent > cap) n_recent = cap;
+        pre = n - n_recent;
+        k = cap - n_recent < pre ? cap - n_recent : pre;
+        for (j = pre; j < n; ++j) keep[j] = 1;
+        for (j = 0; j < pre; ++j) { rk[j].v = mass[(size_t)bh * N + j]; rk[j].idx = j; }
+        qsort(rk, (size_t)pre, sizeof(ranked), by_value_desc_index_asc);
+        for (j = 0; j < k; ++j) keep[rk[j].idx] = 1;
+        for (j = 0; j < n; ++j) {
+            if (!keep[j]) continue;
+            kept[(size_t)bh * cap_rows + m] = j;
+            widen(K, ((size_t)bh * N + j) * d, (size_t)d, dtype, row);
+            memcpy(K_out + ((size_t)bh * cap_rows + m) * d, row, sizeof(double) * (size_t)d);
+            widen(V, ((size_t)bh * N + j) * d, (size_t)d, dtype, row);
+            memcpy(V_out + ((size_t)bh * cap_rows + m) * d, row, sizeof(double) * (size_t)d);
+            ++m;
+        }
+        for (j = m; j < cap_rows; ++j) kept[(size_t)bh * cap_rows + j] = -1;
+        n_kept[bh] = m;
+        free(keep); free(rk); free(row);
+    }
+    return 0;
+}
+
 /* Threads the slice loops run on (for the benchmark's report). */
 int kvm_ref_num_threads(void)
 {

@@ -169,3 +169,24 @@ def merge(K, V, dtype: str, set_start, pivot, n_sets, sigma_mode: int = SIGMA_ME
     if rc:
         raise RuntimeError(f"kvm_ref_merge failed: {rc}")
     return K_out, V_out, w
+
+
+def evict(K, V, mass, dtype: str, budget: float, recent_ratio: float, cap_rows: int, seq_lens=None):
+    """Comparison workload (eviction by score) -> (kept (B, H, cap_rows), n_kept (B, H), K_out, V_out fp64)."""
+    lib = _load()
+    _check_storage(K, dtype)
+    _check_storage(V, dtype)
+    B, H, N, d = K.shape
+    mass = np.ascontiguousarray(mass, dtype=np.float64)
+    sl = _lens(seq_lens, B)
+    kept = np.empty((B, H, cap_rows), np.int32)
+    n_kept = np.empty((B, H), np.int32)
+    K_out = np.zeros((B, H, cap_rows, d), np.float64)
+    V_out = np.zeros((B, H, cap_rows, d), np.float64)
+    lib.kvm_ref_evict.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_double, ctypes.c_double, ctypes.c_int] + \
+        [ctypes.c_void_p] * 7
+    rc = lib.kvm_ref_evict(B, H, N, d, _DTYPE[dtype], _ptr(sl), float(budget), float(recent_ratio), int(cap_rows),
+                           _ptr(K), _ptr(V), _ptr(mass), _ptr(kept), _ptr(n_kept), _ptr(K_out), _ptr(V_out))
+    if rc:
+        raise RuntimeError(f"kvm_ref_evict failed: {rc}")
+    return kept, n_kept, K_out, V_out

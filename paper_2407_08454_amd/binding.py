@@ -24,7 +24,7 @@ KVM_PIVOT_MAX_SCORE, KVM_PIVOT_LAST, KVM_PIVOT_RANDOM = 0, 1, 2
 KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
-           "kvm_identify_sets", "kvm_merge", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
+           "kvm_identify_sets", "kvm_merge", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
 _TORCH_DTYPE = {torch.float32: KVM_F32, torch.float16: KVM_F16, torch.bfloat16: KVM_BF16}
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_merge.restype = ctypes.c_int
+    lib.kvm_evict.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 8 + [S, P]
+    lib.kvm_evict.restype = ctypes.c_int
     lib.kvm_profile_enable.argtypes = [ctypes.c_int32]
     lib.kvm_profile_enable.restype = ctypes.c_int
     lib.kvm_profile_collect.argtypes = [ctypes.POINTER(KvmKernelTime), ctypes.c_int32]
@@ -214,6 +216,25 @@ def kvm_merge(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets
         ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(set_start), _ptr(pivot), _ptr(n_sets),
         _ptr(K_out), _ptr(V_out), _ptr(w_opt), None if ws is None else _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_evict(shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_out, V_out, ws):
+    """Comparison workload: keep the recent window and the largest scores, gather their rows."""
+    _same_device(K, V, mass, kept, n_kept, K_out, V_out, ws)
+    B, H, N, d = shape.B, shape.H_kv, shape.N, shape.d
+    cap = kvm_out_capacity(shape, params)
+    want = {"K": (K, (B, H, N, d)), "V": (V, (B, H, N, d)), "mass": (mass, (B, H, N)), "kept": (kept, (B, H, cap)),
+            "n_kept": (n_kept, (B, H)), "K_out": (K_out, (B, H, cap, d)), "V_out": (V_out, (B, H, cap, d))}
+    for name, (t, shp) in want.items():
+        if tuple(t.shape) != shp:
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {shp}")
+    if kept.dtype != torch.int32 or n_kept.dtype != torch.int32 or mass.dtype != torch.float32:
+        raise ValueError("kept and n_kept must be int32, mass float32")
+    if not (K.dtype == V.dtype == K_out.dtype == V_out.dtype) or _TORCH_DTYPE[K.dtype] != shape.dtype:
+        raise ValueError("dtype mismatch")
+    _check("kvm_evict", load_library().kvm_evict(
+        ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(mass), _ptr(kept), _ptr(n_kept), _ptr(K_out),
+        _ptr(V_out), None if ws is None else _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
 def kvm_profile_enable(max_launches: int):

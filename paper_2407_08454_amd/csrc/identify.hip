@@ -278,6 +278,48 @@ __device__ void block_select_kth_largest(KeyFn key_at, int count, int k, uint32_
     greater = gt;
 }
 
+// flags[j] := 1 for the conserved tokens of a slice -- positions [pre, n) (the recent window)
+// and the n_heavy largest masses among [0, pre) (exact top-k, ties to the lower index) -- and 0
+// for the others.  Whole workgroup; no barrier after the last store.
+__device__ void mark_conserved(const float *mass, uint8_t *flags, int n, int pre, int n_heavy, SegShared &sh)
+{
+    const int tid = threadIdx.x;
+    uint32_t T1 = 0;
+    int take_eq1 = 0;
+    if (n_heavy > 0) {
+        int gt1;
+        block_select_kth_largest([&](int j, uint32_t &key) { key = sortable_key(mass[j]); return true; }, pre,
+                                 n_heavy, T1, gt1, sh);
+        take_eq1 = n_heavy - gt1;
+    }
+    int carry = 0;
+    for (int t0 = 0; t0 < n; t0 += SEG_TILE) {
+        const int jb = t0 + tid * SEG_ITEMS;
+        uint32_t key[SEG_ITEMS];
+        int eq_cnt = 0;
+#pragma unroll
+        for (int i = 0; i < SEG_ITEMS; ++i) {
+            const int j = jb + i;
+            key[i] = (j < pre && n_heavy > 0) ? sortable_key(mass[j]) : 0u;
+            if (j < pre && n_heavy > 0 && key[i] == T1) ++eq_cnt;
+        }
+        int total;
+        int rank = carry + block_exclusive_sum(eq_cnt, total, sh.wave_i);
+#pragma unroll
+        for (int i = 0; i < SEG_ITEMS; ++i) {
+            const int j = jb + i;
+            if (j >= n) break;
+            bool prot = j >= pre;
+            if (!prot && n_heavy > 0) {
+                if (key[i] > T1) prot = true;
+                else if (key[i] == T1) { prot = rank < take_eq1; ++rank; }
+            }
+            flags[j] = prot ? 1 : 0;
+        }
+        carry += total;
+    }
+}
+
 // Random member of a set of m tokens that starts at token lo of a slice: the SplitMix64
 // output function (Steele, Lea, Flood 2014) at the counter seed + slice * 2^32 + lo, upper
 // 32 bits scaled to [0, m).
@@ -331,43 +373,7 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
     if (a.phase != SEG_AFTER_FLAGS) {
     for (int j = n + tid; j < a.N; j += SEG_BLOCK) set_id[j] = -1;
 
-    // ---- conserved tokens: recent window + exact top-k of mass (ties: lower index) ----------
-    uint32_t T1 = 0;
-    int take_eq1 = 0;
-    if (n_heavy > 0) {
-        int gt1;
-        block_select_kth_largest([&](int j, uint32_t &key) { key = sortable_key(mass[j]); return true; }, pre,
-                                 n_heavy, T1, gt1, sh);
-        take_eq1 = n_heavy - gt1;
-    }
-    {
-        int carry = 0;
-        for (int t0 = 0; t0 < n; t0 += SEG_TILE) {
-            const int jb = t0 + tid * SEG_ITEMS;
-            uint32_t key[SEG_ITEMS];
-            int eq_cnt = 0;
-#pragma unroll
-            for (int i = 0; i < SEG_ITEMS; ++i) {
-                const int j = jb + i;
-                key[i] = (j < pre && n_heavy > 0) ? sortable_key(mass[j]) : 0u;
-                if (j < pre && n_heavy > 0 && key[i] == T1) ++eq_cnt;
-            }
-            int total;
-            int rank = carry + block_exclusive_sum(eq_cnt, total, sh.wave_i);
-#pragma unroll
-            for (int i = 0; i < SEG_ITEMS; ++i) {
-                const int j = jb + i;
-                if (j >= n) break;
-                bool prot = j >= pre;
-                if (!prot && n_heavy > 0) {
-                    if (key[i] > T1) prot = true;
-                    else if (key[i] == T1) { prot = rank < take_eq1; ++rank; }
-                }
-                flags[j] = prot ? 1 : 0;
-            }
-            carry += total;
-        }
-    }
+    mark_conserved(mass, flags, n, pre, n_heavy, sh);
     }
     if (a.phase == SEG_FLAGS_ONLY) return;
     __syncthreads();
@@ -574,6 +580,128 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
         a.n_sets[slice] = M;
         a.slice_status[slice] = status;
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// comparison workload: eviction by aggregated attention score
+// ------------------------------------------------------------------------------------------
+
+struct EvictArgs {
+    const float *mass;
+    uint8_t *flags;
+    int32_t *kept, *n_kept;
+    const int32_t *seq_lens;
+    int H, N, cap_rows;
+    double budget, recent_ratio;
+};
+
+// Per slice: keep the recent window and the tokens with the largest masses among the others,
+// floor(budget n) in all; write their positions in ascending order.
+__global__ __launch_bounds__(SEG_BLOCK) void evict_select_kernel(EvictArgs a)
+{
+    __shared__ SegShared sh;
+    const int slice = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int n = clamp_len(a.seq_lens, slice / a.H, a.N);
+    const float *mass = a.mass + (size_t)slice * a.N;
+    uint8_t *flags = a.flags + (size_t)slice * a.N;
+    int32_t *kept = a.kept + (size_t)slice * a.cap_rows;
+    const int cap = min((int)floor(a.budget * (double)n), a.cap_rows);
+    int n_recent = (int)floor(a.recent_ratio * (double)n);
+    if (n_recent > cap) n_recent = cap;                      // a window wider than the budget is cut to it
+    const int pre = n - n_recent;
+    const int n_heavy = min(cap - n_recent, pre);
+    mark_conserved(mass, flags, n, pre, n_heavy, sh);
+    __syncthreads();
+    int carry = 0;
+    for (int t0 = 0; t0 < n; t0 += SEG_TILE) {
+        const int jb = t0 + tid * SEG_ITEMS;
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < SEG_ITEMS; ++i) cnt += (jb + i < n && flags[jb + i]) ? 1 : 0;
+        int total;
+        int pos = carry + block_exclusive_sum(cnt, total, sh.wave_i);
+#pragma unroll
+        for (int i = 0; i < SEG_ITEMS; ++i)
+            if (jb + i < n && flags[jb + i]) kept[pos++] = jb + i;
+        carry += total;
+    }
+    for (int s = carry + tid; s < a.cap_rows; s += SEG_BLOCK) kept[s] = -1;
+    if (tid == 0) a.n_kept[slice] = carry;
+}
+
+// out[s] = in[kept[s]] for the kept rows of K and V; 16 lanes per row.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                           T *__restrict__ K_out, T *__restrict__ V_out,
+                                                           const int32_t *__restrict__ kept, const int32_t *__restrict__ n_kept,
+                                                           int N, int cap_rows, int tiles_per_slice)
+{
+    const int slice = blockIdx.x / tiles_per_slice;
+    const int tile = blockIdx.x - slice * tiles_per_slice;
+    const int c = threadIdx.x & 15, group = threadIdx.x >> 4;
+    const int m = min(max(n_kept[slice], 0), cap_rows);
+    const int32_t *kp = kept + (size_t)slice * cap_rows;
+    constexpr int ROWS = 4;                                  // rows per group, loads in flight together
+    const int s0 = (tile * 16 + group) * ROWS;
+    typename Elem<T>::Raw rk[ROWS], rv[ROWS];
+    int src[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        src[r] = s0 + r < m ? min(max(kp[s0 + r], 0), N - 1) : -1;
+        if (src[r] >= 0) {
+            rk[r] = Elem<T>::load(K + ((size_t)slice * N + src[r]) * HEAD_DIM, c);
+            rv[r] = Elem<T>::load(V + ((size_t)slice * N + src[r]) * HEAD_DIM, c);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+        if (src[r] >= 0) {
+            Elem<T>::store(K_out + ((size_t)slice * cap_rows + s0 + r) * HEAD_DIM, c, rk[r]);
+            Elem<T>::store(V_out + ((size_t)slice * cap_rows + s0 + r) * HEAD_DIM, c, rv[r]);
+        }
+}
+
+template <typename T>
+static void launch_gather(const kvm_shape &sh, int cap_rows, const void *K, const void *V, void *K_out, void *V_out,
+                          const int32_t *kept, const int32_t *n_kept, hipStream_t st)
+{
+    const int tiles = (cap_rows + 63) / 64;
+    const long long blocks = (long long)sh.B * sh.H_kv * tiles;
+    ProfScope prof("gather_rows_kernel", st);
+    hipLaunchKernelGGL(gather_rows_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, (const T *)K, (const T *)V, (T *)K_out,
+                       (T *)V_out, kept, n_kept, sh.N, cap_rows, tiles);
+}
+
+kvm_status launch_evict(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
+                        const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, uint8_t *flags,
+                        hipStream_t st)
+{
+    const long long slices = (long long)sh.B * sh.H_kv;
+    if (slices == 0) return KVM_OK;
+    EvictArgs a;
+    a.mass = mass;
+    a.flags = flags;
+    a.kept = kept;
+    a.n_kept = n_kept;
+    a.seq_lens = sh.seq_lens;
+    a.H = sh.H_kv;
+    a.N = sh.N;
+    a.cap_rows = cap_rows;
+    a.budget = pr.budget;
+    a.recent_ratio = pr.recent_ratio;
+    {
+        ProfScope prof("evict_select_kernel", st);
+        hipLaunchKernelGGL(evict_select_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), 0, st, a);
+    }
+    kvm_status rc = check_launch("evict_select_kernel");
+    if (rc != KVM_OK || cap_rows == 0 || sh.N == 0) return rc;
+    switch (sh.dtype) {
+    case KVM_F32: launch_gather<float>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
+    case KVM_F16: launch_gather<half_t>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
+    default: launch_gather<bf16_t>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
+    }
+    return check_launch("gather_rows_kernel");
 }
 
 // ------------------------------------------------------------------------------------------

@@ -218,6 +218,28 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
                            inv_norm, run, flags, slice_status, (hipStream_t)stream);
 }
 
+kvm_status kvm_evict(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V, const float *mass,
+                     int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, void *ws, size_t ws_bytes, void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_evict");
+    if (rc != KVM_OK) return rc;
+    rc = check_params(params, "kvm_evict");
+    if (rc != KVM_OK) return rc;
+    if (shape->B == 0) return KVM_OK;
+    const int cap = capacity(shape, params);
+    if (!n_kept || (cap > 0 && (!kept || !K_out || !V_out)) || (shape->N > 0 && (!K || !V || !mass))) {
+        set_error("kvm_evict: a required pointer is NULL");
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (ws_identify(shape) > 0 && (!ws || ws_bytes < ws_identify(shape))) {
+        set_error("kvm_evict: workspace of %zu bytes needed, %zu given", ws_identify(shape), ws ? ws_bytes : (size_t)0);
+        return KVM_ERR_WORKSPACE;
+    }
+    const size_t tok = (size_t)shape->B * shape->H_kv * shape->N;
+    uint8_t *flags = (uint8_t *)ws + 3 * align_up(tok * sizeof(float), 256);
+    return launch_evict(*shape, *params, cap, K, V, mass, kept, n_kept, K_out, V_out, flags, (hipStream_t)stream);
+}
+
 kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
                      const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out, void *V_out,
                      float *w_opt, void *ws, size_t ws_bytes, void *stream)

@@ -634,3 +634,38 @@ def test_whole_pass_random_shapes(case):
     Q, K, V = _slices(2000 + case, B, H, lens, N, 128, G, dtype)
     sample = [(b, h) for b in range(B) for h in range(H)]
     _whole_pass(Q, K, V, dtype, G, params, lens, sample, f"random shapes {case}")
+
+
+# ---------------------------------------------------------------------------------------------
+# comparison workload: eviction by score
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_evict_matches_the_oracle(dtype):
+    n = 2100
+    lens = [n, 1000, 0, 1, 77]
+    _say(f"evict: {dtype}, lens {lens}")
+    Q, K, V = _slices(35, 5, 2, lens, n, 128, 1, dtype)
+    rng = np.random.default_rng(9)
+    mass = (rng.random((5, 2, n)) + 0.01).astype(np.float32)
+    mass[0, 0, 300:700] = mass[0, 0, 300]                    # ties: the lower index is kept first
+    for budget, recent in ((0.5, 0.17), (0.35, 0.08), (0.3, 0.3), (1.0, 0.0)):   # plain, plain, window only, keep all
+        params = kb.make_params(budget, recent, 0.0)
+        Kd, Vd = gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+        sh = kb.make_shape(Kd, 1, gu.lens_dev(lens))
+        cap = kb.kvm_out_capacity(sh, params)
+        kept = torch.full((5, 2, cap), -7, dtype=torch.int32, device="cuda")
+        n_kept = torch.full((5, 2), -7, dtype=torch.int32, device="cuda")
+        Ko = torch.zeros((5, 2, cap, 128), dtype=gu.TORCH_DT[dtype], device="cuda")
+        Vo = torch.zeros_like(Ko)
+        ws = torch.empty(kb.kvm_workspace_bytes(sh, params), dtype=torch.uint8, device="cuda")
+        kb.kvm_evict(sh, params, Kd, Vd, torch.from_numpy(mass).cuda(), kept, n_kept, Ko, Vo, ws)
+        torch.cuda.synchronize()
+        ok, on, oko, ovo = ref.evict(K, V, mass.astype(np.float64), dtype, budget, recent, cap, lens)
+        assert np.array_equal(n_kept.cpu().numpy(), on) and np.array_equal(kept.cpu().numpy(), ok)
+        gk, gv = gu.to_host_f64(Ko), gu.to_host_f64(Vo)
+        for b in range(5):
+            for h in range(2):
+                m = int(on[b, h])
+                assert np.array_equal(gk[b, h, :m], oko[b, h, :m]) and np.array_equal(gv[b, h, :m], ovo[b, h, :m])
+                assert (gk[b, h, m:] == 0).all()              # rows beyond the kept ones are not written

@@ -214,3 +214,32 @@ def test_anchor_rule_reports_a_missed_budget_and_truncates():
     assert M > 60 and o["status"][0, 0] == (ref.SLICE_INFEASIBLE | ref.SLICE_TRUNCATED)
     free = _anchor(K, mass, 0.95, recent=0.1, heavy=0.05)
     assert np.array_equal(free["set_start"][0, 0, :61], o["set_start"][0, 0])     # no fallback: same sets, cut off
+
+
+# ---------------------------------------------------------------------------------------------
+# comparison workload: eviction by aggregated attention score (Section 2.3)
+# ---------------------------------------------------------------------------------------------
+
+def test_eviction_keeps_the_recent_window_and_the_largest_scores():
+    rng = np.random.default_rng(5)
+    n, d = 500, 128
+    K = rng.standard_normal((1, 2, n, d)).astype(np.float32)
+    V = rng.standard_normal((1, 2, n, d)).astype(np.float32)
+    mass = rng.uniform(0, 1, (1, 2, n))
+    mass[0, 1, 100:140] = mass[0, 1, 100]                    # a block of ties
+    for budget, recent in ((0.5, 0.17), (0.35, 0.08), (0.1, 0.3), (1.0, 0.0)):
+        cap_rows = math.floor(budget * n)
+        kept, n_kept, ko, vo = ref.evict(K, V, mass, "f32", budget, recent, cap_rows)
+        for h in range(2):
+            n_recent = min(math.floor(recent * n), cap_rows)
+            pre = n - n_recent
+            k = min(cap_rows - n_recent, pre)
+            # restated with numpy: a stable sort by descending score keeps the lower index first
+            order = np.argsort(-mass[0, h, :pre], kind="stable")[:k]
+            want = np.sort(np.concatenate([order, np.arange(pre, n)]))
+            assert n_kept[0, h] == len(want) == cap_rows
+            assert np.array_equal(kept[0, h, :len(want)], want)
+            assert np.array_equal(ko[0, h, :len(want)], K[0, h, want].astype(np.float64))
+            assert np.array_equal(vo[0, h, :len(want)], V[0, h, want].astype(np.float64))
+    kept, n_kept, _, _ = ref.evict(K, V, mass, "f32", 0.5, 0.17, 300, seq_lens=[37])
+    assert n_kept[0, 0] == 18 and (kept[0, :, 18:] == -1).all() and kept[0, 0, 17] == 36
