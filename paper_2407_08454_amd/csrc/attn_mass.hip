@@ -344,13 +344,17 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
     // Workgroup t of a slice takes row tile tiles-1-t, the one with the longest rows left; with
     // fewer workgroups than tiles it then also takes tile t, the shortest left, so that all
     // workgroups of a launch carry the same load.
+    // The repeat launch (redo given, no HOLD) has one workgroup per slice, which looks at all
+    // of the slice's flags.
     const bool paired = wgs_per_slice < tiles_per_slice;
-    for (int pass = 0; pass < 2; ++pass) {
-    const int tile = pass == 0 ? tiles_per_slice - 1 - tm.tile : tm.tile;
-    if (pass == 1 && (!paired || tm.tile >= tiles_per_slice - 1 - tm.tile)) break;
+    const bool repeat = !HOLD && redo;
+    const int passes = repeat ? tiles_per_slice : 2;
+    for (int pass = 0; pass < passes; ++pass) {
+    const int tile = repeat ? pass : (pass == 0 ? tiles_per_slice - 1 - tm.tile : tm.tile);
+    if (!repeat && pass == 1 && (!paired || tm.tile >= tiles_per_slice - 1 - tm.tile)) break;
     const int q_begin = tile * ROWS_PER_BLOCK;
     if (q_begin >= n) continue;
-    if (!HOLD && redo && !redo[(size_t)qslice * tiles_per_slice + tile]) continue;
+    if (repeat && !redo[(size_t)qslice * tiles_per_slice + tile]) continue;
     const int q0 = q_begin + wave * 32 * NB;                  // first query row of this wave
 
     const int q_last = min(q_begin + ROWS_PER_BLOCK, n) - 1; // last valid query row of the workgroup
@@ -663,8 +667,9 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, fl
             kvm_status rc = check_launch("attn_lse_kernel");
             if (rc != KVM_OK) return rc;
             ProfScope prof("attn_lse_redo_kernel", st);
-            hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
-                               (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c);
+            hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)((n_q + 7) / 8 * 8)), dim3(ATT_BLOCK), 0, st,
+                               (const T *)Q, (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad,
+                               tiles, 1, c);
         } else {
             ProfScope prof("attn_lse_kernel", st);
             hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
