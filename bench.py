@@ -53,6 +53,9 @@ def main() -> int:
                     help="evict = the comparison workload: attention mass, then plain eviction by score (kvm_evict)")
     ap.add_argument("--sets", choices=["adjacent", "anchor"], default="adjacent",
                     help="reading of Algorithm 1 (anchor = similarity to the set's top token; no budget fallback)")
+    ap.add_argument("--row-stats", choices=["computed", "given"], default="computed",
+                    help="given = the softmax row statistics are an input, as left behind by a prefill attention kernel "
+                         "(kvm_attn_mass_from_lse: only the column-sum pass runs)")
     ap.add_argument("--sigma", type=float, default=None, help="fixed sigma (Section 5.4) instead of the per-set one")
     ap.add_argument("--gen-workers", type=int, default=None,
                     help="processes that generate the inputs (1 = in this process, e.g. under a profiler)")
@@ -101,19 +104,41 @@ def main() -> int:
     shape = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(shape, params, "cuda", tdt)
 
+    row_lse = None
+    if args.row_stats == "given":
+        # stand-in for what a prefill attention kernel leaves behind: natural-log softmax denominators,
+        # made here with library calls before anything is timed
+        variant += "; row statistics given by the caller"
+        row_lse = torch.empty((B, H * G, N), dtype=torch.float32, device="cuda")
+        upper = torch.triu(torch.ones((N, N), dtype=torch.bool, device="cuda"), 1)
+        for b in range(B):
+            for hq in range(H * G):
+                s_ = (Qd[b, hq].float() @ Kd[b, hq // G].float().T) * (1.0 / d ** 0.5)
+                row_lse[b, hq] = torch.logsumexp(s_.masked_fill_(upper, float("-inf")), dim=1)
+        del upper, s_
+
+    def attn_mass():
+        if row_lse is None:
+            kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+        else:
+            kb.kvm_attn_mass_from_lse(shape, Qd, Kd, row_lse, buf.mass, buf.ws)
+
     evict = args.method == "evict"
     if evict:
-        variant = "comparison workload: eviction by score"
+        variant = "comparison workload: eviction by score" + ("; row statistics given by the caller" if row_lse is not None else "")
         # kept positions go where the pivots would, their count where the set count would
         def rest():
             kb.kvm_evict(shape, params, Kd, Vd, buf.mass, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.ws)
         buf.status.zero_()
     for _ in range(args.warmup):
+        attn_mass()
         if evict:
-            kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
             rest()
         else:
-            kb.compress(shape, params, Qd, Kd, Vd, buf)
+            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, None,
+                                 buf.status, buf.ws)
+            kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None,
+                         buf.ws)
     torch.cuda.synchronize()
     if args.calibration_copy:          # reads and writes K.numel() * element_size bytes exactly once
         copy = torch.empty_like(Kd)
@@ -128,7 +153,7 @@ def main() -> int:
     t0 = time.perf_counter()
     for e in ev:
         e[0].record()
-        kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+        attn_mass()
         e[1].record()
         if evict:
             e[2].record()
@@ -162,7 +187,7 @@ def main() -> int:
     roofline = None
     hbm = {}
     headline = (args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
-                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and not evict)
+                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and not evict and row_lse is None)
 
     def traffic(name):
         return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None

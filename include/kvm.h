@@ -154,6 +154,21 @@ kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, f
                          void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same map for a caller that already holds the softmax row statistics of
+ * Eq. (1), as prefill attention kernels keep them: only the column sums of
+ * Eq. (7) remain, about half of kvm_attn_mass's work.
+ *   row_lse  in  (B, H_kv*G, N) float32: natural logarithm of
+ *                sum over j <= t of exp(q_t . k_j / sqrt(d)) for query row t;
+ *                entries at t >= n_b are not read
+ * Other arguments, workspace and result as for kvm_attn_mass.  The result is
+ * only as good as row_lse: statistics taken from other scores than the stored
+ * Q and K give columns that no longer sum to n_b per query head.
+ */
+kvm_status kvm_attn_mass_from_lse(const kvm_shape *shape, const void *Q, const void *K,
+                                  const float *row_lse, float *mass, void *ws, size_t ws_bytes,
+                                  void *stream);
+
+/*
  * Merging-set identification (Section 3.2; Section 4.1 Def. 4.1 and Algorithm 1;
  * conserved states: Section 4.1 last paragraph and Section 5.1; pivot: Eq. (7)).
  * Per slice, with n = n_b:

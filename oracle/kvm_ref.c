@@ -174,6 +174,49 @@ int kvm_ref_attn_mass(int B, int H, int G, int N, int d, int dtype, const int32_
     return 0;
 }
 
+/* Row statistics of Eq. (1): lse[b, hq, t] = log of the sum over keys j <= t of
+ * exp(q_t . k_j / sqrt(d)), i.e. the logarithm of the softmax denominator of query row t
+ * (the quantity attention kernels keep per row).  Q: (B, H*G, N, d), K: (B, H, N, d),
+ * lse: (B, H*G, N) fp64; rows >= n_b get 0. */
+int kvm_ref_row_lse(int B, int H, int G, int N, int d, int dtype, const int32_t *seq_lens,
+                    const void *Q, const void *K, double *lse)
+{
+    int bq;
+    if (B < 0 || H < 1 || G < 1 || N < 0 || d < 1 || !lse) return 1;
+    if (B && N && (!Q || !K)) return 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bq = 0; bq < B * H * G; ++bq) {
+        const int b = bq / (H * G), h = (bq % (H * G)) / G;
+        const int n = valid_len(seq_lens, b, N);
+        const double scale = 1.0 / sqrt((double)d);
+        double *out = lse + (size_t)bq * N;
+        double *kd, *qd, *row;
+        int t, j, c;
+        for (t = 0; t < N; ++t) out[t] = 0.0;
+        if (n == 0) continue;
+        kd = (double *)malloc(sizeof(double) * (size_t)n * d);
+        qd = (double *)malloc(sizeof(double) * (size_t)n * d);
+        row = (double *)malloc(sizeof(double) * (size_t)n);
+        widen(K, ((size_t)b * H + h) * N * d, (size_t)n * d, dtype, kd);
+        widen(Q, (size_t)bq * N * d, (size_t)n * d, dtype, qd);
+        for (t = 0; t < n; ++t) {
+            double mx = -INFINITY, sum = 0.0;
+            for (j = 0; j <= t; ++j) {
+                double sc = 0.0;
+                for (c = 0; c < d; ++c) sc += qd[(size_t)t * d + c] * kd[(size_t)j * d + c];
+                row[j] = sc * scale;
+                if (row[j] > mx) mx = row[j];
+            }
+            for (j = 0; j <= t; ++j) sum += exp(row[j] - mx);
+            out[t] = mx + log(sum);
+        }
+        free(kd);
+        free(qd);
+        free(row);
+    }
+    return 0;
+}
+
 /* ========================================================================= */
 /* (b) merging-set identification                                             */
 /* ========================================================================= */

@@ -105,6 +105,22 @@ def attn_mass(Q, K, dtype: str, G: int = 1, seq_lens=None):
     return mass
 
 
+def row_lse(Q, K, dtype: str, G: int = 1, seq_lens=None):
+    """Q (B, H*G, N, d), K (B, H, N, d) -> natural-log softmax denominators (B, H*G, N) fp64."""
+    lib = _load()
+    _check_storage(Q, dtype)
+    _check_storage(K, dtype)
+    B, H, N, d = K.shape
+    assert Q.shape == (B, H * G, N, d)
+    sl = _lens(seq_lens, B)
+    lse = np.empty((B, H * G, N), dtype=np.float64)
+    lib.kvm_ref_row_lse.argtypes = [ctypes.c_int] * 6 + [ctypes.c_void_p] * 4
+    rc = lib.kvm_ref_row_lse(B, H, G, N, d, _DTYPE[dtype], _ptr(sl), _ptr(Q), _ptr(K), _ptr(lse))
+    if rc:
+        raise RuntimeError(f"kvm_ref_row_lse failed: {rc}")
+    return lse
+
+
 def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy_ratio: float,
                   threshold: float, enforce_budget: bool = True, cap_rows: int | None = None,
                   seq_lens=None, pivot_rule: int = PIVOT_MAX_SCORE, pivot_seed: int = 0,

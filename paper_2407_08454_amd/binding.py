@@ -24,6 +24,7 @@ KVM_PIVOT_MAX_SCORE, KVM_PIVOT_LAST, KVM_PIVOT_RANDOM = 0, 1, 2
 KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
+           "kvm_attn_mass_from_lse",
            "kvm_identify_sets", "kvm_merge", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
@@ -73,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_workspace_bytes.restype = S
     lib.kvm_attn_mass.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, S, P]
     lib.kvm_attn_mass.restype = ctypes.c_int
+    lib.kvm_attn_mass_from_lse.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, P, S, P]
+    lib.kvm_attn_mass_from_lse.restype = ctypes.c_int
     lib.kvm_identify_sets.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
@@ -156,16 +159,31 @@ def _same_device(*ts):
             raise ValueError("tensors must share one device")
 
 
-def kvm_attn_mass(shape: KvmShape, Q, K, mass, ws):
-    """mass (B, H_kv, N) float32 <- aggregated attention score of every key."""
-    _same_device(Q, K, mass, ws)
+def _check_attn_operands(shape: KvmShape, Q, K, mass):
     B, H, G, N, d = shape.B, shape.H_kv, shape.G, shape.N, shape.d
     if tuple(Q.shape) != (B, H * G, N, d) or tuple(K.shape) != (B, H, N, d) or tuple(mass.shape) != (B, H, N):
         raise ValueError("operand shapes do not match the shape descriptor")
     if mass.dtype != torch.float32 or Q.dtype != K.dtype or _TORCH_DTYPE[K.dtype] != shape.dtype:
         raise ValueError("dtype mismatch")
+
+
+def kvm_attn_mass(shape: KvmShape, Q, K, mass, ws):
+    """mass (B, H_kv, N) float32 <- aggregated attention score of every key."""
+    _same_device(Q, K, mass, ws)
+    _check_attn_operands(shape, Q, K, mass)
     _check("kvm_attn_mass", load_library().kvm_attn_mass(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(mass), _ptr(ws),
                                                          ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_attn_mass_from_lse(shape: KvmShape, Q, K, row_lse, mass, ws):
+    """The same map from the caller's row statistics: row_lse (B, H_kv*G, N) float32, natural logarithms."""
+    _same_device(Q, K, row_lse, mass, ws)
+    _check_attn_operands(shape, Q, K, mass)
+    if row_lse.dtype != torch.float32 or tuple(row_lse.shape) != (shape.B, shape.H_kv * shape.G, shape.N):
+        raise ValueError("row_lse must be float32 of shape (B, H_kv*G, N)")
+    _check("kvm_attn_mass_from_lse",
+           load_library().kvm_attn_mass_from_lse(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(row_lse), _ptr(mass), _ptr(ws),
+                                                 ws.numel() * ws.element_size(), _stream()))
 
 
 def kvm_identify_sets(shape: KvmShape, params: KvmParams, K, mass, set_id, set_start, pivot, n_sets, sim_opt,

@@ -643,15 +643,38 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
 
 int attn_lse_stride(int N);
 
+// Row statistics handed in by the caller: natural-log sums, one per query row, without padding.
+// They are copied into the padded base-2 layout that the column-sum kernel streams; rows past
+// the slice's length get +inf, which makes their terms vanish.
+__global__ void __launch_bounds__(256) lse_import_kernel(const float *__restrict__ row_lse, float *__restrict__ lse,
+                                                         const int32_t *__restrict__ seq_lens, int HG, int N, int n_pad,
+                                                         int blocks_per_slice)
+{
+    const int qslice = blockIdx.x / blocks_per_slice;
+    const int q = (blockIdx.x % blocks_per_slice) * 256 + threadIdx.x;
+    if (q >= n_pad) return;
+    int n = seq_lens ? seq_lens[qslice / HG] : N;
+    n = n < 0 ? 0 : (n > N ? N : n);
+    lse[(size_t)qslice * n_pad + q] = q < n ? row_lse[(size_t)qslice * N + q] * 1.44269504088896341f : INFINITY;
+}
+
 template <typename T>
-static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse, hipStream_t st)
+static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass, float *lse,
+                           hipStream_t st)
 {
     constexpr int ROWS = ATT_WAVES * 32 * Mma<T>::NBLK;
     const int tiles = (sh.N + ROWS - 1) / ROWS;
     const float c = (float)(1.4426950408889634 / sqrt((double)sh.d));
     const int n_q = sh.B * sh.H_kv * sh.G, n_kv = sh.B * sh.H_kv;
     const int n_pad = attn_lse_stride(sh.N);
-    {
+    if (row_lse) {
+        ProfScope prof("lse_import_kernel", st);
+        const int per = (n_pad + 255) / 256;
+        hipLaunchKernelGGL(lse_import_kernel, dim3((unsigned)((long long)per * n_q)), dim3(256), 0, st, row_lse, lse,
+                           sh.seq_lens, sh.H_kv * sh.G, sh.N, n_pad, per);
+        kvm_status rc = check_launch("lse_import_kernel");
+        if (rc != KVM_OK) return rc;
+    } else {
         // long sequences: half as many workgroups, each with one long and one short row tile
         // (measured faster from 8 tiles per slice on; below that the second tile's start-up,
         // which nothing overlaps, costs more than the even load gains)
@@ -694,13 +717,16 @@ int attn_lse_stride(int N) { return (N + 63) / 64 * 64; }
 // Row tiles per slice, for the flags that follow the row statistics in the workspace.
 int attn_row_tiles(int N) { return (N + 255) / 256; }
 
-kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse, hipStream_t st)
+// row_lse == nullptr: the row statistics are computed here (first score pass); otherwise the
+// caller's are imported and only the column-sum pass runs.
+kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass, float *lse,
+                            hipStream_t st)
 {
     if ((long long)sh.B * sh.H_kv == 0 || sh.N == 0) return KVM_OK;
     switch (sh.dtype) {
-    case KVM_F32: return launch_t<float>(sh, Q, K, mass, lse, st);
-    case KVM_F16: return launch_t<half_t>(sh, Q, K, mass, lse, st);
-    default: return launch_t<bf16_t>(sh, Q, K, mass, lse, st);
+    case KVM_F32: return launch_t<float>(sh, Q, K, row_lse, mass, lse, st);
+    case KVM_F16: return launch_t<half_t>(sh, Q, K, row_lse, mass, lse, st);
+    default: return launch_t<bf16_t>(sh, Q, K, row_lse, mass, lse, st);
     }
 }
 

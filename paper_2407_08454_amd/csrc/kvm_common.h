@@ -145,8 +145,8 @@ struct ProfScope {
     ~ProfScope();
 };
 
-kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, float *mass, float *lse,
-                            hipStream_t st);
+kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass,
+                            float *lse, hipStream_t st);
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,
                            const float *mass, int32_t *set_id, int32_t *set_start, int32_t *pivot,
                            int32_t *n_sets, float *sim, float *inv_norm, int32_t *run, uint8_t *flags,

@@ -44,6 +44,19 @@ def gpu_mass(Q, K, dtype, G=1, seq_lens=None):
     return mass.cpu().numpy()
 
 
+def gpu_mass_from_lse(Q, K, row_lse32, dtype, G=1, seq_lens=None):
+    Qd, Kd = to_dev(Q, dtype), to_dev(K, dtype)
+    sl = lens_dev(seq_lens)
+    sh = kb.make_shape(Kd, G, sl)
+    B, H, N, _ = K.shape
+    mass = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(kb.kvm_workspace_bytes(sh), 256), dtype=torch.uint8, device="cuda")
+    ld = torch.from_numpy(np.ascontiguousarray(row_lse32, dtype=np.float32)).cuda()
+    kb.kvm_attn_mass_from_lse(sh, Qd, Kd, ld, mass, ws)
+    torch.cuda.synchronize()
+    return mass.cpu().numpy()
+
+
 def gpu_identify(K, mass32, dtype, params, seq_lens=None, want_sim=True):
     Kd = to_dev(K, dtype)
     sl = lens_dev(seq_lens)

@@ -78,6 +78,14 @@ def test_host_detectable_errors_return_before_any_launch():
     assert attn(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"workspace" in lib.kvm_last_error()
     assert lib.kvm_attn_mass(None, one, one, one, one, 0, None) == kb.KVM_ERR_INVALID_ARG
 
+    def attn_lse(sh, row_lse=one, ws=one, nbytes=1 << 30):
+        return lib.kvm_attn_mass_from_lse(ctypes.byref(sh), one, one, row_lse, one, ws, nbytes, None)
+
+    assert attn_lse(_shape(d=64)) == kb.KVM_ERR_UNSUPPORTED
+    assert attn_lse(_shape(), row_lse=None) == kb.KVM_ERR_INVALID_ARG and b"row_lse" in lib.kvm_last_error()
+    assert attn_lse(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"kvm_attn_mass_from_lse" in lib.kvm_last_error()
+    assert attn_lse(_shape(N=0), row_lse=None, ws=None) == kb.KVM_OK          # nothing to do
+
     def ident(sh, pr, ws=one, nbytes=1 << 30, K=one):
         return lib.kvm_identify_sets(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, None, one, ws,
                                      nbytes, None)

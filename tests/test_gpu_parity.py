@@ -122,6 +122,24 @@ def test_mass_large_scores_do_not_overflow():
     assert (np.abs(got - want)[big] / want[big]).max() <= gu.TOL
 
 
+@pytest.mark.parametrize("dtype,G,lens,N", [("f16", 1, [600], 600), ("bf16", 4, [300, 129, 0, 1, 256], 320),
+                                            ("f32", 2, [257, 64], 257), ("f16", 1, [2100, 1500], 2100)])
+def test_mass_from_row_statistics_of_the_caller(dtype, G, lens, N):
+    """The row statistics come from the oracle (rounded to fp32, as a prefill kernel would hand
+    them over); entries past a slice's length are poisoned to show that they are not read."""
+    _say(f"mass from row statistics dtype={dtype} G={G} lens={lens} N={N}")
+    Q, K, _ = _slices(14, len(lens), 2, lens, N, 128, G, dtype)
+    lse = ref.row_lse(Q, K, dtype, G=G, seq_lens=lens).astype(np.float32)
+    for b, n in enumerate(lens):
+        lse[b, :, n:] = np.nan
+    want = ref.attn_mass(Q, K, dtype, G=G, seq_lens=lens)
+    got = gu.gpu_mass_from_lse(Q, K, lse, dtype, G=G, seq_lens=lens)
+    gu.assert_mass_close(got, want, lens, N, f"{dtype} G={G} from row statistics")
+    # and it is the map that the two-pass entry point computes
+    two_pass = gu.gpu_mass(Q, K, dtype, G=G, seq_lens=lens)
+    assert np.abs(got - two_pass).max() <= 1e-4 * max(1.0, np.abs(two_pass).max())
+
+
 # ---------------------------------------------------------------------------------------------
 # (b) merging sets
 # ---------------------------------------------------------------------------------------------

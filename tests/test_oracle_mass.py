@@ -117,3 +117,56 @@ def test_ragged_lengths_ignore_padding():
         assert (a[b, 0, n:] == 0).all()
         if n:
             np.testing.assert_allclose(a[b, 0, :n], _brute(Q[b, 0, :n], K[b, 0, :n], "f16"), rtol=1e-12)
+
+
+# ---- row statistics (the logarithm of the softmax denominator of Eq. (1)) ----
+
+@pytest.mark.parametrize("n", [1, 5, 130])
+def test_row_lse_of_zero_queries_is_log_of_row_length(n):
+    K = _rand((1, 1, n, 16), "f32", 3)
+    Q = np.zeros((1, 1, n, 16), np.float32)
+    lse = ref.row_lse(Q, K, "f32")[0, 0]
+    np.testing.assert_allclose(lse, np.log(np.arange(1, n + 1)), rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_row_lse_against_library_logsumexp(dtype):
+    from scipy.special import logsumexp
+    n, d, G = 37, 24, 2
+    K = _rand((2, 3, n, d), dtype, 11)
+    Q = _rand((2, 3 * G, n, d), dtype, 12)
+    lse = ref.row_lse(Q, K, dtype, G=G)
+    for b in range(2):
+        for hq in range(3 * G):
+            s = synth.to_f64(Q[b, hq], dtype) @ synth.to_f64(K[b, hq // G], dtype).T / math.sqrt(d)
+            s[np.triu(np.ones((n, n), dtype=bool), 1)] = -np.inf
+            np.testing.assert_allclose(lse[b, hq], logsumexp(s, axis=1), rtol=1e-13, atol=1e-13)
+
+
+def test_row_lse_survives_scores_that_overflow_exp():
+    # identical unit-direction keys scaled so that every score is 800: exp overflows, the log does not
+    n, d = 9, 4
+    K = np.zeros((1, 1, n, d), np.float32)
+    K[..., 0] = 40.0
+    Q = K.copy()
+    lse = ref.row_lse(Q, K, "f32")[0, 0]
+    np.testing.assert_allclose(lse, 800.0 + np.log(np.arange(1, n + 1)), rtol=1e-15)
+
+
+def test_row_lse_and_mass_describe_the_same_map():
+    # column j of the map is exp(s_tj - lse_t) summed over rows t >= j: ties the two oracle functions together
+    n, d, G = 50, 8, 2
+    lens = np.array([50, 31], np.int32)
+    K = _rand((2, 2, n, d), "f16", 21)
+    Q = _rand((2, 2 * G, n, d), "f16", 22)
+    lse = ref.row_lse(Q, K, "f16", G=G, seq_lens=lens)
+    mass = ref.attn_mass(Q, K, "f16", G=G, seq_lens=lens)
+    for b in range(2):
+        m = int(lens[b])
+        assert np.all(lse[b, :, m:] == 0.0)
+        for h in range(2):
+            col = np.zeros(m)
+            for g in range(G):
+                s = synth.to_f64(Q[b, h * G + g, :m], "f16") @ synth.to_f64(K[b, h, :m], "f16").T / math.sqrt(d)
+                col += np.where(np.tril(np.ones((m, m), dtype=bool)), np.exp(s - lse[b, h * G + g, :m, None]), 0.0).sum(axis=0)
+            np.testing.assert_allclose(mass[b, h, :m], col, rtol=1e-12)
