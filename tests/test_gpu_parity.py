@@ -334,6 +334,33 @@ def test_identify_infeasible_budget_is_reported():
     assert g["status"][0, 0] == want and g["n_sets"][0, 0] > g["cap_rows"]
 
 
+@pytest.mark.parametrize("rule", ["adjacent", "anchor"])
+def test_identify_and_merge_beyond_the_short_sequence_paths(rule):
+    """40000 tokens: longer than any staging buffer sized for the usual prompts (the anchor walk
+    reads its inputs from global memory from 16385 tokens on), with a ragged second row."""
+    n = 40000
+    lens = [n, 33333]
+    _say(f"identify + merge, {rule} sets, N={n}, lens {lens}")
+    Q, K, V = _slices(27, 2, 2, lens, n, 128, 1, "f16")
+    del Q
+    mass = np.random.default_rng(10).random((2, 2, n)) ** 3 + 1e-3
+    params = kb.kvm_params_for_budget(0.5)
+    if rule == "anchor":
+        params.set_rule = kb.KVM_SETS_ANCHOR
+    g, o = _identify_both(K, mass, "f16", params, lens)
+    np.testing.assert_allclose(g["sim"], o["sim"], atol=2e-6)
+    if rule == "anchor":
+        exc = _compare_anchor_maps(g, o, "long anchor")
+    else:
+        exc, _ = gu.compare_maps(g, o, lens, n, params.threshold, "long adjacent")
+    _say(f"  excused slices {exc}; sets {o['n_sets'].tolist()}")
+    assert exc <= 1
+    gu.check_partition(g, lens, n, g["cap_rows"])
+    o["cap_rows"] = g["cap_rows"]
+    res = _merge_both(K, V, "f16", params, o, lens)
+    _check_merge(K, V, "f16", o, *res, f"long {rule}")
+
+
 # ---------------------------------------------------------------------------------------------
 # (c) Gaussian-kernel merge
 # ---------------------------------------------------------------------------------------------
