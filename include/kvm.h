@@ -81,7 +81,7 @@ typedef enum {
                                  similar enough (chain of adjacent tokens)                    */
     KVM_SETS_ANCHOR = 1       /* tokens below the set's top token join, one after the other,
                                  as long as they are similar enough to that top token
-                                 (Section 3.2: the states similar to "a given key state")     */
+                                 (Section 3.2: similarity to one given key state)             */
 } kvm_set_rule;
 
 typedef struct {

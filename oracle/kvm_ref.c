@@ -26,8 +26,8 @@
  *         iff their cosine similarity exceeds the threshold; then i moves down.
  *         The other reading is available as a variant (REF_SETS_ANCHOR): the set of
  *         token i takes the tokens below it, one after the other, as long as their
- *         similarity to k_i itself exceeds the threshold (Section 3.2 speaks of the
- *         states similar to "a given key state"); the first token that fails becomes
+ *         similarity to k_i itself exceeds the threshold (Section 3.2 groups the states
+ *         by their similarity to one given key state); the first token that fails becomes
  *         the next i.  No budget fallback exists for this reading.
  *   R-b3  a zero-norm key has similarity 0 to its neighbours.
  *   R-b4  conserved tokens are singleton sets in their original position and
@@ -39,7 +39,7 @@
  *         tokens with the largest similarity are removed until it fits.
  *   R-c1  sigma of a set = (sum of Euclidean distances to the pivot) /
  *         (sqrt(2) |S|)  (Eq. (5) defines sigma through g, which itself needs
- *         sigma; Section 5.4 reports sigma "around 5", impossible for a mean of
+ *         sigma; Section 5.4 reports a computed sigma near 5, impossible for a mean of
  *         values in (0,1]).  PARITY UNPINNED against the authors' own code.
  *   R-c3  sigma == 0 (all keys of the set equal the pivot) gives g = 1.
  *   R-c4  value weights are the key weights times |S| (Section 4.2), optional.
