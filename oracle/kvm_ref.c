@@ -217,6 +217,55 @@ int kvm_ref_row_lse(int B, int H, int G, int N, int d, int dtype, const int32_t 
     return 0;
 }
 
+/* Decode-time update of the aggregated scores (Eq. (1) for the newest query alone; the column
+ * sums of Eq. (7) are sums over query rows, so one more row is one more term per key).  For
+ * every batch row with n = n_b >= 1 valid tokens, the newest token sits at position n-1 and its
+ * query states are q_new[b, h*G+g, :]:
+ *     p_g = softmax over j in [0, n) of q_g . k_j / sqrt(d),
+ *     mass[b,h,j] += sum_g p_g[j]  for j < n-1,      mass[b,h,n-1] = sum_g p_g[n-1].
+ * Positions >= n are left alone.  q_new: (B, H*G, d), K: (B, H, N, d), mass: (B, H, N) fp64. */
+int kvm_ref_attn_mass_append(int B, int H, int G, int N, int d, int dtype, const int32_t *seq_lens,
+                             const void *q_new, const void *K, double *mass)
+{
+    int bh;
+    if (B < 0 || H < 1 || G < 1 || N < 0 || d < 1 || !mass) return 1;
+    if (B && N && (!q_new || !K)) return 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bh = 0; bh < B * H; ++bh) {
+        const int b = bh / H, h = bh % H;
+        const int n = valid_len(seq_lens, b, N);
+        const double scale = 1.0 / sqrt((double)d);
+        double *a = mass + (size_t)bh * N;
+        double *kd, *qd, *row;
+        int g, j, c;
+        if (n == 0) continue;
+        kd = (double *)malloc(sizeof(double) * (size_t)n * d);
+        qd = (double *)malloc(sizeof(double) * (size_t)d);
+        row = (double *)malloc(sizeof(double) * (size_t)n);
+        widen(K, (size_t)bh * N * d, (size_t)n * d, dtype, kd);
+        a[n - 1] = 0.0;
+        for (g = 0; g < G; ++g) {
+            double mx = -INFINITY, sum = 0.0;
+            widen(q_new, ((size_t)b * H * G + (size_t)h * G + g) * d, (size_t)d, dtype, qd);
+            for (j = 0; j < n; ++j) {
+                double sc = 0.0;
+                for (c = 0; c < d; ++c) sc += qd[c] * kd[(size_t)j * d + c];
+                row[j] = sc * scale;
+                if (row[j] > mx) mx = row[j];
+            }
+            for (j = 0; j < n; ++j) {
+                row[j] = exp(row[j] - mx);
+                sum += row[j];
+            }
+            for (j = 0; j < n; ++j) a[j] += row[j] / sum;
+        }
+        free(kd);
+        free(qd);
+        free(row);
+    }
+    return 0;
+}
+
 /* ========================================================================= */
 /* (b) merging-set identification                                             */
 /* ========================================================================= */

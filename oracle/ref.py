@@ -121,6 +121,23 @@ def row_lse(Q, K, dtype: str, G: int = 1, seq_lens=None):
     return lse
 
 
+def attn_mass_append(q_new, K, mass, dtype: str, G: int = 1, seq_lens=None):
+    """q_new (B, H*G, d), K (B, H, N, d), mass (B, H, N) -> mass with the newest token's attention row added (fp64 copy)."""
+    lib = _load()
+    _check_storage(q_new, dtype)
+    _check_storage(K, dtype)
+    B, H, N, d = K.shape
+    assert q_new.shape == (B, H * G, d)
+    sl = _lens(seq_lens, B)
+    out = np.array(mass, dtype=np.float64, order="C", copy=True)
+    assert out.shape == (B, H, N)
+    lib.kvm_ref_attn_mass_append.argtypes = [ctypes.c_int] * 6 + [ctypes.c_void_p] * 4
+    rc = lib.kvm_ref_attn_mass_append(B, H, G, N, d, _DTYPE[dtype], _ptr(sl), _ptr(q_new), _ptr(K), _ptr(out))
+    if rc:
+        raise RuntimeError(f"kvm_ref_attn_mass_append failed: {rc}")
+    return out
+
+
 def identify_sets(K, mass, dtype: str, budget: float, recent_ratio: float, heavy_ratio: float,
                   threshold: float, enforce_budget: bool = True, cap_rows: int | None = None,
                   seq_lens=None, pivot_rule: int = PIVOT_MAX_SCORE, pivot_seed: int = 0,

@@ -170,3 +170,52 @@ def test_row_lse_and_mass_describe_the_same_map():
                 s = synth.to_f64(Q[b, h * G + g, :m], "f16") @ synth.to_f64(K[b, h, :m], "f16").T / math.sqrt(d)
                 col += np.where(np.tril(np.ones((m, m), dtype=bool)), np.exp(s - lse[b, h * G + g, :m, None]), 0.0).sum(axis=0)
             np.testing.assert_allclose(mass[b, h, :m], col, rtol=1e-12)
+
+
+# ---- decode-time update: one more query row (Eq. (1) for the newest token, added into Eq. (7)) ----
+
+@pytest.mark.parametrize("dtype,G", [("f32", 1), ("f16", 2), ("bf16", 4)])
+def test_append_continues_the_prefill_scores(dtype, G):
+    # the column sums over n query rows are those over n-1 rows plus the last row: the batch function on
+    # the longer prompt must equal the batch function on the shorter one followed by appends
+    n0, n1, d = 23, 29, 32
+    K = _rand((2, 2, n1, d), dtype, 31)
+    Q = _rand((2, 2 * G, n1, d), dtype, 32)
+    mass = ref.attn_mass(Q, K, dtype, G=G, seq_lens=[n0, n0])
+    for n in range(n0 + 1, n1 + 1):
+        mass = ref.attn_mass_append(np.ascontiguousarray(Q[:, :, n - 1]), K, mass, dtype, G=G, seq_lens=[n, n])
+    np.testing.assert_allclose(mass, ref.attn_mass(Q, K, dtype, G=G), rtol=1e-12, atol=1e-14)
+
+
+def test_append_with_a_zero_query_spreads_one_over_the_tokens():
+    n, N = 10, 14
+    K = _rand((1, 1, N, 8), "f32", 33)
+    q = np.zeros((1, 3, 8), np.float32)                       # three query heads on the one KV head
+    mass = np.arange(N, dtype=np.float64)[None, None].copy()
+    got = ref.attn_mass_append(q, K, mass, "f32", G=3, seq_lens=[n])[0, 0]
+    want = np.arange(N, dtype=np.float64)
+    want[:n - 1] += 3.0 / n
+    want[n - 1] = 3.0 / n                                     # the newest token's entry is set, not added to
+    np.testing.assert_allclose(got, want, rtol=1e-14)         # and positions past the length are left alone
+
+
+def test_append_row_is_a_library_softmax_and_picks_the_matching_key():
+    n, d = 40, 16
+    K = _rand((1, 1, n, d), "f32", 34)
+    q = np.ascontiguousarray(K[:, :, 17] * 8.0)               # strongly aligned with key 17
+    got = ref.attn_mass_append(q, K, np.zeros((1, 1, n)), "f32")[0, 0]
+    p = softmax(q[0, 0].astype(np.float64) @ K[0, 0].astype(np.float64).T / math.sqrt(d))
+    np.testing.assert_allclose(got, p, rtol=1e-12)
+    assert got.argmax() == 17 and got[17] > 0.99 and got.sum() == pytest.approx(1.0, rel=1e-13)
+
+
+def test_append_ragged_rows_empty_and_single_token():
+    N, d = 6, 8
+    K = _rand((3, 2, N, d), "f16", 35)
+    q = _rand((3, 2, d), "f16", 36)
+    before = np.full((3, 2, N), 7.0)
+    got = ref.attn_mass_append(q, K, before, "f16", seq_lens=[0, 1, 6])
+    assert np.all(got[0] == 7.0)                              # no token: untouched
+    assert np.all(got[1, :, 0] == 1.0) and np.all(got[1, :, 1:] == 7.0)   # a single token attends to itself
+    assert np.allclose(got[2].sum(axis=1) - 7.0 * (N - 1), 1.0)
+    assert np.all(before == 7.0)                              # the input array is not modified
