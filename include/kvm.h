@@ -169,6 +169,26 @@ kvm_status kvm_attn_mass_from_lse(const kvm_shape *shape, const void *Q, const v
                                   void *stream);
 
 /*
+ * Decode-time update of the aggregated attention score: one more query row of
+ * Eq. (1) added into the column sums of Eq. (7), so that `mass` stays what
+ * kvm_attn_mass would give on the longer sequence without another pass over the
+ * prompt.  (The paper runs its method on the prefilled cache and says nothing
+ * of decoding; this call only keeps the scores current, the sets and the merge
+ * are then refreshed with the two calls below.)
+ * Per batch row, n_b = seq_lens[b] counts the newest token, whose key is already
+ * stored at K[b, :, n_b - 1]:
+ *     p_g = softmax over j < n_b of q_new[b, h*G+g] . K[b,h,j] / sqrt(d),
+ *     mass[b,h,j] += sum_g p_g[j] for j < n_b - 1;   mass[b,h,n_b-1] = sum_g p_g[n_b-1].
+ *   q_new  in      (B, H_kv*G, d) dtype: query states of the newest token
+ *   K      in      (B, H_kv, N, d) dtype
+ *   mass   in/out  (B, H_kv, N) float32; entries at j >= n_b are not touched, rows
+ *                  with n_b == 0 are skipped
+ * Workspace as for kvm_attn_mass.  Deterministic.
+ */
+kvm_status kvm_attn_mass_append(const kvm_shape *shape, const void *q_new, const void *K,
+                                float *mass, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Merging-set identification (Section 3.2; Section 4.1 Def. 4.1 and Algorithm 1;
  * conserved states: Section 4.1 last paragraph and Section 5.1; pivot: Eq. (7)).
  * Per slice, with n = n_b:

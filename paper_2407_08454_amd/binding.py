@@ -24,7 +24,7 @@ KVM_PIVOT_MAX_SCORE, KVM_PIVOT_LAST, KVM_PIVOT_RANDOM = 0, 1, 2
 KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
-           "kvm_attn_mass_from_lse",
+           "kvm_attn_mass_from_lse", "kvm_attn_mass_append",
            "kvm_identify_sets", "kvm_merge", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
@@ -76,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_attn_mass.restype = ctypes.c_int
     lib.kvm_attn_mass_from_lse.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, P, S, P]
     lib.kvm_attn_mass_from_lse.restype = ctypes.c_int
+    lib.kvm_attn_mass_append.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, S, P]
+    lib.kvm_attn_mass_append.restype = ctypes.c_int
     lib.kvm_identify_sets.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
@@ -184,6 +186,19 @@ def kvm_attn_mass_from_lse(shape: KvmShape, Q, K, row_lse, mass, ws):
     _check("kvm_attn_mass_from_lse",
            load_library().kvm_attn_mass_from_lse(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(row_lse), _ptr(mass), _ptr(ws),
                                                  ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_attn_mass_append(shape: KvmShape, q_new, K, mass, ws):
+    """mass (B, H_kv, N) float32 += the attention row of the newest token (its key already stored at n_b - 1)."""
+    _same_device(q_new, K, mass, ws)
+    B, H, G, N, d = shape.B, shape.H_kv, shape.G, shape.N, shape.d
+    if tuple(q_new.shape) != (B, H * G, d) or tuple(K.shape) != (B, H, N, d) or tuple(mass.shape) != (B, H, N):
+        raise ValueError("operand shapes do not match the shape descriptor")
+    if mass.dtype != torch.float32 or q_new.dtype != K.dtype or _TORCH_DTYPE[K.dtype] != shape.dtype:
+        raise ValueError("dtype mismatch")
+    _check("kvm_attn_mass_append",
+           load_library().kvm_attn_mass_append(ctypes.byref(shape), _ptr(q_new), _ptr(K), _ptr(mass), _ptr(ws),
+                                               ws.numel() * ws.element_size(), _stream()))
 
 
 def kvm_identify_sets(shape: KvmShape, params: KvmParams, K, mass, set_id, set_start, pivot, n_sets, sim_opt,

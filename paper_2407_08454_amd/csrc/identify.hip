@@ -24,42 +24,6 @@ constexpr int COS_GROUPS = COS_BLOCK / 16;                  // 16-lane groups pe
 constexpr int COS_ROWS_PER_GROUP = 16;                      // consecutive rows per 16-lane group
 constexpr int COS_ROWS_PER_BLOCK = COS_GROUPS * COS_ROWS_PER_GROUP;
 
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-// partial dot product of a lane's 8 elements of two rows, fp32 accumulation (products of two
-// 16-bit values are exact in fp32)
-template <typename T> struct RowDot;
-template <> struct RowDot<half_t> {
-    static __device__ __forceinline__ float dot(const Elem<half_t>::Raw &a, const Elem<half_t>::Raw &b) {
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t ai = a.v[i], bi = b.v[i];
-            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ai), __builtin_bit_cast(f16x2, bi), s, false);
-        }
-        return s;
-    }
-};
-template <> struct RowDot<bf16_t> {
-    static __device__ __forceinline__ float dot(const Elem<bf16_t>::Raw &a, const Elem<bf16_t>::Raw &b) {
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t ai = a.v[i], bi = b.v[i];
-            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ai), __builtin_bit_cast(bf16x2, bi), s, false);
-        }
-        return s;
-    }
-};
-template <> struct RowDot<float> {
-    static __device__ __forceinline__ float dot(const Elem<float>::Raw &a, const Elem<float>::Raw &b) {
-        float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { s0 = fmaf(a.a[i], b.a[i], s0); s1 = fmaf(a.b[i], b.b[i], s1); }
-        return s0 + s1;
-    }
-};
 
 // 1/sqrt(x) for a squared norm; 0 when the squared norm is zero or below the normal fp32 range
 // (such a key counts as a zero-norm key: its similarities are 0)

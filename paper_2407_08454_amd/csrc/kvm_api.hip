@@ -120,9 +120,10 @@ static int capacity(const kvm_shape *sh, const kvm_params *pr)
 
 static size_t ws_attn(const kvm_shape *sh)
 {
-    // row statistics, then one flag per (query slice, row tile)
+    // row statistics, then one flag per (query slice, row tile); the decode-time update keeps its
+    // scores in the first part and two floats per (query slice, tile) in the second
     const size_t q_slices = (size_t)sh->B * sh->H_kv * sh->G;
-    return align_up(q_slices * attn_lse_stride(sh->N) * sizeof(float) + q_slices * attn_row_tiles(sh->N) * sizeof(int32_t), 256);
+    return align_up(q_slices * attn_lse_stride(sh->N) * sizeof(float) + q_slices * attn_row_tiles(sh->N) * 2 * sizeof(float), 256);
 }
 static size_t ws_identify(const kvm_shape *sh)
 {
@@ -203,6 +204,20 @@ kvm_status kvm_attn_mass_from_lse(const kvm_shape *shape, const void *Q, const v
                                   void *ws, size_t ws_bytes, void *stream)
 {
     return attn_mass_entry("kvm_attn_mass_from_lse", shape, Q, K, row_lse, true, mass, ws, ws_bytes, stream);
+}
+
+kvm_status kvm_attn_mass_append(const kvm_shape *shape, const void *q_new, const void *K, float *mass, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_attn_mass_append");
+    if (rc != KVM_OK) return rc;
+    if ((long long)shape->B * shape->N == 0) return KVM_OK;
+    if (!q_new || !K || !mass) { set_error("kvm_attn_mass_append: q_new, K and mass must not be NULL"); return KVM_ERR_INVALID_ARG; }
+    if (!ws || ws_bytes < ws_attn(shape)) {
+        set_error("kvm_attn_mass_append: workspace of %zu bytes needed, %zu given", ws_attn(shape), ws ? ws_bytes : (size_t)0);
+        return KVM_ERR_WORKSPACE;
+    }
+    return launch_attn_append(*shape, q_new, K, mass, (float *)ws, (hipStream_t)stream);
 }
 
 kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, const void *K, const float *mass,

@@ -98,6 +98,43 @@ template <> struct Elem<float> {
     }
 };
 
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// partial dot product of a lane's 8 elements of two rows, fp32 accumulation (products of two
+// 16-bit values are exact in fp32)
+template <typename T> struct RowDot;
+template <> struct RowDot<half_t> {
+    static __device__ __forceinline__ float dot(const Elem<half_t>::Raw &a, const Elem<half_t>::Raw &b) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t ai = a.v[i], bi = b.v[i];
+            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ai), __builtin_bit_cast(f16x2, bi), s, false);
+        }
+        return s;
+    }
+};
+template <> struct RowDot<bf16_t> {
+    static __device__ __forceinline__ float dot(const Elem<bf16_t>::Raw &a, const Elem<bf16_t>::Raw &b) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t ai = a.v[i], bi = b.v[i];
+            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ai), __builtin_bit_cast(bf16x2, bi), s, false);
+        }
+        return s;
+    }
+};
+template <> struct RowDot<float> {
+    static __device__ __forceinline__ float dot(const Elem<float>::Raw &a, const Elem<float>::Raw &b) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { s0 = fmaf(a.a[i], b.a[i], s0); s1 = fmaf(a.b[i], b.b[i], s1); }
+        return s0 + s1;
+    }
+};
+
 // ---- cross-lane helpers -------------------------------------------------------------
 
 // DPP move within a row of 16 lanes; every lane is enabled so no old value is needed.
@@ -147,6 +184,7 @@ struct ProfScope {
 
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass,
                             float *lse, hipStream_t st);
+kvm_status launch_attn_append(const kvm_shape &sh, const void *q_new, const void *K, float *mass, float *ws, hipStream_t st);
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,
                            const float *mass, int32_t *set_id, int32_t *set_start, int32_t *pivot,
                            int32_t *n_sets, float *sim, float *inv_norm, int32_t *run, uint8_t *flags,

@@ -57,6 +57,17 @@ def gpu_mass_from_lse(Q, K, row_lse32, dtype, G=1, seq_lens=None):
     return mass.cpu().numpy()
 
 
+def gpu_mass_append(q_new, K, mass32, dtype, G=1, seq_lens=None):
+    qd, Kd = to_dev(q_new, dtype), to_dev(K, dtype)
+    sl = lens_dev(seq_lens)
+    sh = kb.make_shape(Kd, G, sl)
+    mass = torch.from_numpy(np.ascontiguousarray(mass32, dtype=np.float32)).cuda()
+    ws = torch.empty(max(kb.kvm_workspace_bytes(sh), 256), dtype=torch.uint8, device="cuda")
+    kb.kvm_attn_mass_append(sh, qd, Kd, mass, ws)
+    torch.cuda.synchronize()
+    return mass.cpu().numpy()
+
+
 def gpu_identify(K, mass32, dtype, params, seq_lens=None, want_sim=True):
     Kd = to_dev(K, dtype)
     sl = lens_dev(seq_lens)

@@ -86,6 +86,14 @@ def test_host_detectable_errors_return_before_any_launch():
     assert attn_lse(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"kvm_attn_mass_from_lse" in lib.kvm_last_error()
     assert attn_lse(_shape(N=0), row_lse=None, ws=None) == kb.KVM_OK          # nothing to do
 
+    def append(sh, q=one, ws=one, nbytes=1 << 30):
+        return lib.kvm_attn_mass_append(ctypes.byref(sh), q, one, one, ws, nbytes, None)
+
+    assert append(_shape(d=64)) == kb.KVM_ERR_UNSUPPORTED
+    assert append(_shape(), q=None) == kb.KVM_ERR_INVALID_ARG and b"q_new" in lib.kvm_last_error()
+    assert append(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"kvm_attn_mass_append" in lib.kvm_last_error()
+    assert append(_shape(N=0), q=None, ws=None) == kb.KVM_OK                     # nothing to do
+
     def ident(sh, pr, ws=one, nbytes=1 << 30, K=one):
         return lib.kvm_identify_sets(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, None, one, ws,
                                      nbytes, None)

@@ -140,6 +140,59 @@ def test_mass_from_row_statistics_of_the_caller(dtype, G, lens, N):
     assert np.abs(got - two_pass).max() <= 1e-4 * max(1.0, np.abs(two_pass).max())
 
 
+@pytest.mark.parametrize("dtype,G,lens,N", [("f16", 1, [600], 600), ("bf16", 4, [300, 129, 0, 1, 256, 257], 320),
+                                            ("f32", 2, [255, 64], 257), ("f16", 1, [5000, 4097], 5000)])
+def test_mass_append_one_query_row(dtype, G, lens, N):
+    """Decode-time update: the same fp32 scores before the call on both sides (random, with a
+    marker past each row's length that must survive), the newest token's query from the generator."""
+    _say(f"mass append dtype={dtype} G={G} lens={lens} N={N}")
+    Q, K, _ = _slices(15, len(lens), 2, lens, N, 128, G, dtype)
+    q_new = np.ascontiguousarray(np.stack([Q[b, :, max(n - 1, 0)] for b, n in enumerate(lens)]))
+    before = (np.random.default_rng(16).random((len(lens), 2, N)) * 3 + 0.01).astype(np.float32)
+    for b, n in enumerate(lens):
+        before[b, :, n:] = -5.0
+    want = ref.attn_mass_append(q_new, K, before.astype(np.float64), dtype, G=G, seq_lens=lens)
+    got = gu.gpu_mass_append(q_new, K, before, dtype, G=G, seq_lens=lens)
+    for b, n in enumerate(lens):
+        assert np.all(got[b, :, n:] == -5.0), "entries past the length were touched"
+        if n:
+            rel = np.abs(got[b, :, :n] - want[b, :, :n]) / want[b, :, :n]
+            assert rel.max() <= gu.TOL, f"row {b}: relative error {rel.max():.3e}"
+            # the row that was added sums to G
+            added = got[b, :, :n].astype(np.float64).sum(axis=1) - before[b, :, :n - 1].astype(np.float64).sum(axis=1)
+            assert added == pytest.approx(G, rel=1e-3)
+
+
+def test_mass_append_continues_the_prefill_pass():
+    """Prefill scores of the first n0 tokens, then appends token by token: the result has to be
+    the prefill scores of all n1 tokens (both from the library; the oracle checks the end state)."""
+    n0, n1, dtype = 300, 316, "f16"
+    _say(f"mass: prefill of {n0} tokens + {n1 - n0} appends against a prefill of {n1}")
+    Q, K, _ = _slices(17, 1, 3, [n1], n1, 128, 1, dtype)
+    mass = gu.gpu_mass(Q, K, dtype, seq_lens=[n0])
+    assert np.all(mass[:, :, n0:] == 0)
+    for n in range(n0 + 1, n1 + 1):
+        mass = gu.gpu_mass_append(np.ascontiguousarray(Q[:, :, n - 1]), K, mass, dtype, seq_lens=[n])
+    want = ref.attn_mass(Q, K, dtype)
+    gu.assert_mass_close(mass, want, None, n1, "prefill + appends")
+    direct = gu.gpu_mass(Q, K, dtype)
+    assert np.abs(mass - direct).max() <= 1e-4 * np.abs(direct).max()
+
+
+def test_mass_append_large_scores():
+    n, dtype = 700, "bf16"
+    _say("mass append: scores in the hundreds")
+    rng = np.random.default_rng(18)
+    k = rng.standard_normal((1, 2, n, 128)).astype(np.float32) * 5
+    q = k[:, :, 123] * 4                                      # the query picks out key 123 with a score near 5000
+    K, q_new = synth.to_storage(k, dtype), synth.to_storage(np.ascontiguousarray(q), dtype)
+    before = np.ones((1, 2, n), np.float32)
+    want = ref.attn_mass_append(q_new, K, before.astype(np.float64), dtype)
+    got = gu.gpu_mass_append(q_new, K, before, dtype)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= gu.TOL * np.abs(want).max() and got[0, 0, 123] == pytest.approx(2.0, rel=1e-3)
+
+
 # ---------------------------------------------------------------------------------------------
 # (b) merging sets
 # ---------------------------------------------------------------------------------------------
