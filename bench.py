@@ -49,8 +49,10 @@ def main() -> int:
                     help="merge weights (average = the average weighted merging of Section 4.2)")
     ap.add_argument("--pivot", choices=["max-score", "last", "random"], default="max-score",
                     help="pivot rule (last = largest index, Section 4.2; random = Section 5.4)")
-    ap.add_argument("--method", choices=["merge", "evict"], default="merge",
-                    help="evict = the comparison workload: attention mass, then plain eviction by score (kvm_evict)")
+    ap.add_argument("--method", choices=["merge", "evict", "append"], default="merge",
+                    help="evict = the comparison workload: attention mass, then plain eviction by score (kvm_evict); "
+                         "append = decode-time refresh: one more query row added to the scores (kvm_attn_mass_append), "
+                         "then sets and merge again")
     ap.add_argument("--sets", choices=["adjacent", "anchor"], default="adjacent",
                     help="reading of Algorithm 1 (anchor = similarity to the set's top token; no budget fallback)")
     ap.add_argument("--row-stats", choices=["computed", "given"], default="computed",
@@ -117,8 +119,18 @@ def main() -> int:
                 row_lse[b, hq] = torch.logsumexp(s_.masked_fill_(upper, float("-inf")), dim=1)
         del upper, s_
 
+    append = args.method == "append"
+    if append:
+        # the prompt's scores once, untimed; every step then treats the last token as newly arrived
+        variant += "; decode-time refresh (one query row per step, then sets and merge)"
+        q_new = Qd[:, :, N - 1].contiguous() if lens is None else torch.stack(
+            [Qd[b, :, max(int(n) - 1, 0)] for b, n in enumerate(lens)]).contiguous()
+        kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+
     def attn_mass():
-        if row_lse is None:
+        if append:
+            kb.kvm_attn_mass_append(shape, q_new, Kd, buf.mass, buf.ws)
+        elif row_lse is None:
             kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
         else:
             kb.kvm_attn_mass_from_lse(shape, Qd, Kd, row_lse, buf.mass, buf.ws)
@@ -187,7 +199,7 @@ def main() -> int:
     roofline = None
     hbm = {}
     headline = (args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
-                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and not evict and row_lse is None)
+                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None)
 
     def traffic(name):
         return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None
@@ -205,7 +217,9 @@ def main() -> int:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                         "frac": ach / PEAK_HBM, "traffic": traffic(dom), "algorithmic_bytes": byts,
                         "ms_per_launch": kernels[dom]}
-        for name, byts in (("cosine_scan_kernel", bytes_cos), ("merge_kernel", bytes_merge)):
+        bytes_app = float(token_slices * d * esz + G * token_slices * 4)     # K once, the scores written
+        for name, byts in (("cosine_scan_kernel", bytes_cos), ("merge_kernel", bytes_merge),
+                           ("append_scores_kernel", bytes_app)):
             if name in kernels:
                 hbm[name] = {"algorithmic_GB": byts / 1e9, "traffic": traffic(name), "ms": kernels[name],
                              "GB/s": byts / (kernels[name] * 1e-3) / 1e9,
@@ -224,21 +238,31 @@ def main() -> int:
         Qs = np.ascontiguousarray(Q.reshape(B * H, G, N, d)[idx])
         ls = None if lens is None else lens[idx // H]
         t0 = time.perf_counter()
-        m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
+        if append:
+            # scores before the step: seeded positive numbers (the oracle's time does not depend on them)
+            m0 = np.random.default_rng(0).random((S, 1, N)) + 0.01
+            qn = np.ascontiguousarray(Qs[:, :, N - 1] if ls is None else
+                                      np.stack([Qs[i, :, max(int(n) - 1, 0)] for i, n in enumerate(ls)]))
+            m = ref.attn_mass_append(qn, Ks, m0, dtype, G=G, seq_lens=ls)
+        else:
+            m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
         o = ref.identify_sets(Ks, m.astype(np.float32).astype(np.float64), dtype, params.budget, params.recent_ratio,
                               params.heavy_ratio, params.threshold, True, buf.cap, ls, pivot_rule=params.pivot_rule,
                               pivot_seed=params.pivot_seed, set_rule=params.set_rule)
         ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
                   bool(params.value_scale_by_set_size), seq_lens=ls, weights=params.weights)
         cpu_s = time.perf_counter() - t0
-        toks = int(N * S if ls is None else ls.sum())
+        toks = S if append else int(N * S if ls is None else ls.sum())
         cores = ref.num_threads()
         cpu = {"value": toks / cpu_s, "unit": "token-slices/s", "cores": cores, "kind": "oracle",
-               "sample": f"{S} of {B * H} slices (evenly spaced over layers and heads), whole pass in fp64, "
+               "sample": f"{S} of {B * H} slices (evenly spaced over layers and heads), {'one decode-time refresh' if append else 'whole pass'} in fp64, "
                          f"{cpu_s:.1f} s wall on {cores} OpenMP threads"}
 
+    metric, work = METRIC, token_slices
+    if append:                                              # one token per slice and step
+        metric, work = "decode-time refresh: appended tokens/sec (all layers x heads) at Llama2-7B N=4096", B * H
     out = {
-        "metric": METRIC, "value": token_slices / (ms_per_step * 1e-3), "unit": "token-slices/s", "n_gpus": 1,
+        "metric": metric, "value": work / (ms_per_step * 1e-3), "unit": "token-slices/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg['name']}: {B // cfg['batch']} layers x {H} KV heads, "
