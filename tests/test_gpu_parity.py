@@ -767,3 +767,72 @@ def test_evict_matches_the_oracle(dtype):
                 m = int(on[b, h])
                 assert np.array_equal(gk[b, h, :m], oko[b, h, :m]) and np.array_equal(gv[b, h, :m], ovo[b, h, :m])
                 assert (gk[b, h, m:] == 0).all()              # rows beyond the kept ones are not written
+
+
+# ---------------------------------------------------------------------------------------------
+# streams and graphs: the calls only enqueue work on the caller's stream
+# ---------------------------------------------------------------------------------------------
+
+def _outputs(buf):
+    names = ("mass", "set_id", "set_start", "pivot", "n_sets", "status", "K_out", "V_out")
+    return {k: getattr(buf, k).clone() for k in names}
+
+
+def _same_outputs(a, b, what):
+    M = a["n_sets"].clamp(max=a["K_out"].shape[2])
+    for k in ("mass", "set_id", "set_start", "pivot", "n_sets", "status"):
+        assert torch.equal(a[k], b[k]), f"{what}: {k} differs"
+    for k in ("K_out", "V_out"):                      # rows past the set count are not written
+        for bb in range(M.shape[0]):
+            for h in range(M.shape[1]):
+                m = int(M[bb, h])
+                assert torch.equal(a[k][bb, h, :m], b[k][bb, h, :m]), f"{what}: {k} differs in slice ({bb},{h})"
+
+
+@pytest.mark.parametrize("rule", ["adjacent", "anchor"])
+def test_whole_pass_on_a_side_stream_and_replayed_from_a_graph(rule):
+    """Nothing in the three calls allocates, synchronises or leaves the caller's stream: the pass
+    can be enqueued on a side stream and captured into a graph.  Every replay (with other work
+    and synchronisations in between, and with new inputs in the same buffers) has to give the
+    bits of the plain run on the same inputs; the kernels use no atomics."""
+    _say(f"whole pass, {rule} sets: side stream, then graph capture and three replays")
+    n, dtype = 1300, "f16"
+    inputs = [_slices(seed, 1, 4, [n], n, 128, 1, dtype) for seed in (41, 42)]
+    dev = [[gu.to_dev(x, dtype) for x in trio] for trio in inputs]
+    params = kb.kvm_params_for_budget(0.5)
+    if rule == "anchor":
+        params.set_rule = kb.KVM_SETS_ANCHOR
+        params.enforce_budget = 0
+    Qs, Ks, Vs = (torch.empty_like(t) for t in dev[0])      # the buffers the graph reads
+    shape = kb.make_shape(Ks, 1, None)
+    buf = kb.Buffers(shape, params, "cuda", torch.float16)
+    plain = []
+    for Qd, Kd, Vd in dev:                                  # default stream, no graph
+        Qs.copy_(Qd), Ks.copy_(Kd), Vs.copy_(Vd)
+        kb.compress(shape, params, Qs, Ks, Vs, buf)
+        torch.cuda.synchronize()
+        plain.append(_outputs(buf))
+    assert not torch.equal(plain[0]["set_id"], plain[1]["set_id"])
+
+    side = torch.cuda.Stream()
+    Qs.copy_(dev[0][0]), Ks.copy_(dev[0][1]), Vs.copy_(dev[0][2])
+    buf.mass.fill_(-1.0)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        kb.compress(shape, params, Qs, Ks, Vs, buf)
+    side.synchronize()
+    _same_outputs(_outputs(buf), plain[0], "side stream")
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        kb.compress(shape, params, Qs, Ks, Vs, buf)
+    for which in (1, 0, 1):
+        Qs.copy_(dev[which][0]), Ks.copy_(dev[which][1]), Vs.copy_(dev[which][2])
+        buf.mass.fill_(-1.0)
+        buf.set_id.fill_(-9)
+        graph.replay()
+        torch.cuda.synchronize()
+        _same_outputs(_outputs(buf), plain[which], f"graph replay with input {which}")
+        # unrelated work of the program between the replays
+        other = gu.gpu_mass(inputs[which][0], inputs[which][1], dtype)
+        assert np.isfinite(other).all()
