@@ -106,7 +106,7 @@ def main() -> int:
     shape = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(shape, params, "cuda", tdt)
 
-    row_lse = None
+    row_lse = sim_carried = None
     if args.row_stats == "given":
         # stand-in for what a prefill attention kernel leaves behind: natural-log softmax denominators,
         # made here with library calls before anything is timed
@@ -126,10 +126,16 @@ def main() -> int:
         q_new = Qd[:, :, N - 1].contiguous() if lens is None else torch.stack(
             [Qd[b, :, max(int(n) - 1, 0)] for b, n in enumerate(lens)]).contiguous()
         kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+        # the similarities are carried from call to call: all of them once, then one per step
+        sim_carried = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
+                             buf.status, buf.ws)
+        params.sim_given = 0 if args.sets == "anchor" else 1       # the anchor rule needs the key norms of a scan
 
     def attn_mass():
         if append:
             kb.kvm_attn_mass_append(shape, q_new, Kd, buf.mass, buf.ws)
+            kb.kvm_sim_append(shape, Kd, sim_carried)
         elif row_lse is None:
             kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
         else:
@@ -147,7 +153,7 @@ def main() -> int:
         if evict:
             rest()
         else:
-            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, None,
+            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
                                  buf.status, buf.ws)
             kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None,
                          buf.ws)
@@ -171,7 +177,7 @@ def main() -> int:
             e[2].record()
             rest()
         else:
-            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, None,
+            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
                                  buf.status, buf.ws)
             e[2].record()
             kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None,

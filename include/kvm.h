@@ -107,7 +107,10 @@ typedef struct {
     int32_t pivot_rule;       /* kvm_pivot_rule                                               */
     uint64_t pivot_seed;      /* seed of the draws of KVM_PIVOT_RANDOM                        */
     int32_t set_rule;         /* kvm_set_rule                                                 */
-    int32_t reserved;         /* set to 0                                                     */
+    int32_t sim_given;        /* 1: sim_opt already holds the adjacent similarities of every
+                                 token below n_b (written by an earlier kvm_identify_sets and
+                                 extended by kvm_sim_append); step 2 below is skipped.  Needs
+                                 sim_opt and set_rule == KVM_SETS_ADJACENT.  0: computed here   */
 } kvm_params;
 
 /*
@@ -117,7 +120,7 @@ typedef struct {
  * budgets in (0,1] get recent = 0.34 beta, heavy = 0.24 beta (the 0.50 row
  * scaled).  Sets sigma_mode = MEAN_DIST, value_scale_by_set_size = 1,
  * enforce_budget = 1, weights = GAUSSIAN, pivot_rule = MAX_SCORE, pivot_seed = 0,
- * set_rule = ADJACENT.
+ * set_rule = ADJACENT, sim_given = 0.
  * Host call.  KVM_ERR_INVALID_ARG if out == NULL or budget
  * is not in (0,1].
  */
@@ -187,6 +190,17 @@ kvm_status kvm_attn_mass_from_lse(const kvm_shape *shape, const void *Q, const v
  */
 kvm_status kvm_attn_mass_append(const kvm_shape *shape, const void *q_new, const void *K,
                                 float *mass, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Decode-time companion of kvm_attn_mass_append for the similarities: only the
+ * newest token's similarity to its predecessor (Eq. (2)) is new, so
+ *     sim[b,h,n_b-1] = cosine(K[b,h,n_b-2], K[b,h,n_b-1])   (0 if n_b == 1 or a norm is 0)
+ * is written, with the bits kvm_identify_sets would write there, and nothing else.
+ * A following kvm_identify_sets with params.sim_given = 1 then reads K not at all.
+ *   K    in      (B, H_kv, N, d) dtype
+ *   sim  in/out  (B, H_kv, N) float32
+ */
+kvm_status kvm_sim_append(const kvm_shape *shape, const void *K, float *sim, void *stream);
 
 /*
  * Merging-set identification (Section 3.2; Section 4.1 Def. 4.1 and Algorithm 1;

@@ -24,7 +24,7 @@ KVM_PIVOT_MAX_SCORE, KVM_PIVOT_LAST, KVM_PIVOT_RANDOM = 0, 1, 2
 KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
-           "kvm_attn_mass_from_lse", "kvm_attn_mass_append",
+           "kvm_attn_mass_from_lse", "kvm_attn_mass_append", "kvm_sim_append",
            "kvm_identify_sets", "kvm_merge", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
@@ -41,7 +41,7 @@ class KvmParams(ctypes.Structure):
                 ("threshold", ctypes.c_float), ("sigma_mode", ctypes.c_int32), ("sigma", ctypes.c_float),
                 ("value_scale_by_set_size", ctypes.c_int32), ("enforce_budget", ctypes.c_int32),
                 ("weights", ctypes.c_int32), ("pivot_rule", ctypes.c_int32), ("pivot_seed", ctypes.c_uint64),
-                ("set_rule", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("set_rule", ctypes.c_int32), ("sim_given", ctypes.c_int32)]
 
 
 class KvmKernelTime(ctypes.Structure):
@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_attn_mass_from_lse.restype = ctypes.c_int
     lib.kvm_attn_mass_append.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, S, P]
     lib.kvm_attn_mass_append.restype = ctypes.c_int
+    lib.kvm_sim_append.argtypes = [ctypes.POINTER(KvmShape), P, P, P]
+    lib.kvm_sim_append.restype = ctypes.c_int
     lib.kvm_identify_sets.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
@@ -117,10 +119,10 @@ def kvm_params_for_budget(budget: float) -> KvmParams:
 
 def make_params(budget, recent_ratio, heavy_ratio, threshold=0.75, sigma_mode=KVM_SIGMA_MEAN_DIST, sigma=0.0,
                 value_scale_by_set_size=True, enforce_budget=True, weights=KVM_WEIGHTS_GAUSSIAN,
-                pivot_rule=KVM_PIVOT_MAX_SCORE, pivot_seed=0, set_rule=KVM_SETS_ADJACENT) -> KvmParams:
+                pivot_rule=KVM_PIVOT_MAX_SCORE, pivot_seed=0, set_rule=KVM_SETS_ADJACENT, sim_given=False) -> KvmParams:
     return KvmParams(float(budget), float(recent_ratio), float(heavy_ratio), float(threshold), int(sigma_mode),
                      float(sigma), int(bool(value_scale_by_set_size)), int(bool(enforce_budget)), int(weights),
-                     int(pivot_rule), int(pivot_seed), int(set_rule), 0)
+                     int(pivot_rule), int(pivot_seed), int(set_rule), int(bool(sim_given)))
 
 
 def make_shape(K: torch.Tensor, G: int = 1, seq_lens: torch.Tensor | None = None) -> KvmShape:
@@ -199,6 +201,17 @@ def kvm_attn_mass_append(shape: KvmShape, q_new, K, mass, ws):
     _check("kvm_attn_mass_append",
            load_library().kvm_attn_mass_append(ctypes.byref(shape), _ptr(q_new), _ptr(K), _ptr(mass), _ptr(ws),
                                                ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_sim_append(shape: KvmShape, K, sim):
+    """sim[b, h, n_b - 1] <- cosine similarity of the newest key and its predecessor; nothing else is written."""
+    _same_device(K, sim)
+    B, H, N, d = shape.B, shape.H_kv, shape.N, shape.d
+    if tuple(K.shape) != (B, H, N, d) or tuple(sim.shape) != (B, H, N):
+        raise ValueError("operand shapes do not match the shape descriptor")
+    if sim.dtype != torch.float32 or _TORCH_DTYPE[K.dtype] != shape.dtype:
+        raise ValueError("dtype mismatch")
+    _check("kvm_sim_append", load_library().kvm_sim_append(ctypes.byref(shape), _ptr(K), _ptr(sim), _stream()))
 
 
 def kvm_identify_sets(shape: KvmShape, params: KvmParams, K, mass, set_id, set_start, pivot, n_sets, sim_opt,

@@ -84,6 +84,29 @@ __global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restr
     }
 }
 
+// Decode time: only the similarity of the newest token to its predecessor is new.  One 16-lane
+// group per slice; nothing but sim[n-1] is written.
+template <typename T>
+__global__ __launch_bounds__(256) void sim_append_kernel(const T *__restrict__ K, float *__restrict__ sim,
+                                                         const int32_t *__restrict__ seq_lens, int H, int N, int slices)
+{
+    const int slice = blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (slice >= slices) return;
+    const int c = threadIdx.x & 15;
+    const int n = clamp_len(seq_lens, slice / H, N);
+    if (n == 0) return;
+    float s = 0.f;
+    if (n >= 2) {                                            // uniform over the 16 lanes of the group
+        const T *Ks = K + (size_t)slice * N * HEAD_DIM;
+        const typename Elem<T>::Raw a = Elem<T>::load(Ks + (size_t)(n - 2) * HEAD_DIM, c);
+        const typename Elem<T>::Raw b = Elem<T>::load(Ks + (size_t)(n - 1) * HEAD_DIM, c);
+        const float dot = row16_sum(RowDot<T>::dot(b, a));
+        const float ra = inv_norm(row16_sum(RowDot<T>::dot(a, a))), rb = inv_norm(row16_sum(RowDot<T>::dot(b, b)));
+        s = (dot * rb) * ra;                                 // the order of the scan kernel: same bits
+    }
+    if (c == 0) sim[(size_t)slice * N + n - 1] = s;
+}
+
 // ------------------------------------------------------------------------------------------
 // anchor rule: run lengths
 // ------------------------------------------------------------------------------------------
@@ -693,6 +716,20 @@ static void launch_anchor_run(const kvm_shape &sh, const void *K, const float *i
                        run, sh.seq_lens, sh.H_kv, sh.N, tiles, eps);
 }
 
+kvm_status launch_sim_append(const kvm_shape &sh, const void *K, float *sim, hipStream_t st)
+{
+    const long long slices = (long long)sh.B * sh.H_kv;
+    if (slices == 0 || sh.N == 0) return KVM_OK;
+    const dim3 grid((unsigned)((slices + 15) / 16)), block(256);
+    ProfScope prof("sim_append_kernel", st);
+    switch (sh.dtype) {
+    case KVM_F32: hipLaunchKernelGGL(sim_append_kernel<float>, grid, block, 0, st, (const float *)K, sim, sh.seq_lens, sh.H_kv, sh.N, (int)slices); break;
+    case KVM_F16: hipLaunchKernelGGL(sim_append_kernel<half_t>, grid, block, 0, st, (const half_t *)K, sim, sh.seq_lens, sh.H_kv, sh.N, (int)slices); break;
+    default: hipLaunchKernelGGL(sim_append_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)K, sim, sh.seq_lens, sh.H_kv, sh.N, (int)slices); break;
+    }
+    return check_launch("sim_append_kernel");
+}
+
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const float *mass,
                            int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets, float *sim,
                            float *inv_norm, int32_t *run, uint8_t *flags, int32_t *slice_status, hipStream_t st)
@@ -700,7 +737,7 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
     const long long slices = (long long)sh.B * sh.H_kv;
     if (slices == 0) return KVM_OK;
     const bool anchor = pr.set_rule == KVM_SETS_ANCHOR;
-    if (sh.N > 0) {
+    if (sh.N > 0 && !pr.sim_given) {
         float *rn = anchor ? inv_norm : nullptr;
         switch (sh.dtype) {
         case KVM_F32: launch_cosine<float>(sh, K, sim, rn, st); break;

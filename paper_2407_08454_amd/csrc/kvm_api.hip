@@ -158,7 +158,7 @@ kvm_status kvm_params_for_budget(double budget, kvm_params *out)
     out->pivot_rule = KVM_PIVOT_MAX_SCORE;
     out->pivot_seed = 0;
     out->set_rule = KVM_SETS_ADJACENT;
-    out->reserved = 0;
+    out->sim_given = 0;
     return KVM_OK;
 }
 
@@ -220,6 +220,15 @@ kvm_status kvm_attn_mass_append(const kvm_shape *shape, const void *q_new, const
     return launch_attn_append(*shape, q_new, K, mass, (float *)ws, (hipStream_t)stream);
 }
 
+kvm_status kvm_sim_append(const kvm_shape *shape, const void *K, float *sim, void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_sim_append");
+    if (rc != KVM_OK) return rc;
+    if ((long long)shape->B * shape->N == 0) return KVM_OK;
+    if (!K || !sim) { set_error("kvm_sim_append: K and sim must not be NULL"); return KVM_ERR_INVALID_ARG; }
+    return launch_sim_append(*shape, K, sim, (hipStream_t)stream);
+}
+
 kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, const void *K, const float *mass,
                              int32_t *set_id, int32_t *set_start, int32_t *pivot, int32_t *n_sets, float *sim_opt,
                              int32_t *slice_status, void *ws, size_t ws_bytes, void *stream)
@@ -230,8 +239,12 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
     if (rc != KVM_OK) return rc;
     if (shape->B == 0) return KVM_OK;
     if (!set_start || !n_sets || !slice_status || (capacity(shape, params) > 0 && !pivot) ||
-        (shape->N > 0 && (!K || !mass || !set_id))) {
+        (shape->N > 0 && ((!K && !params->sim_given) || !mass || !set_id))) {
         set_error("kvm_identify_sets: a required pointer is NULL");
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (params->sim_given && (!sim_opt || params->set_rule != KVM_SETS_ADJACENT)) {
+        set_error("kvm_identify_sets: sim_given needs sim_opt and the adjacent set rule");
         return KVM_ERR_INVALID_ARG;
     }
     if (ws_identify(shape) > 0 && (!ws || ws_bytes < ws_identify(shape))) {

@@ -185,6 +185,7 @@ struct ProfScope {
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass,
                             float *lse, hipStream_t st);
 kvm_status launch_attn_append(const kvm_shape &sh, const void *q_new, const void *K, float *mass, float *ws, hipStream_t st);
+kvm_status launch_sim_append(const kvm_shape &sh, const void *K, float *sim, hipStream_t st);
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,
                            const float *mass, int32_t *set_id, int32_t *set_start, int32_t *pivot,
                            int32_t *n_sets, float *sim, float *inv_norm, int32_t *run, uint8_t *flags,

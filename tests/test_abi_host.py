@@ -107,6 +107,11 @@ def test_host_detectable_errors_return_before_any_launch():
     assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, pivot_rule=3)) == kb.KVM_ERR_UNSUPPORTED
     assert ident(_shape(), kb.make_params(0.5, 0.1, 0.1, set_rule=2)) == kb.KVM_ERR_UNSUPPORTED and \
         b"set_rule" in lib.kvm_last_error()
+    given = kb.make_params(0.5, 0.1, 0.1, sim_given=True)
+    assert ident(_shape(), given) == kb.KVM_ERR_INVALID_ARG and b"sim_given" in lib.kvm_last_error()   # no sim_opt passed
+    assert lib.kvm_sim_append(ctypes.byref(_shape()), None, one, None) == kb.KVM_ERR_INVALID_ARG
+    assert lib.kvm_sim_append(ctypes.byref(_shape(d=64)), one, one, None) == kb.KVM_ERR_UNSUPPORTED
+    assert lib.kvm_sim_append(ctypes.byref(_shape(N=0)), None, None, None) == kb.KVM_OK
     assert ident(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
     assert ident(_shape(), p, nbytes=8) == kb.KVM_ERR_WORKSPACE
 

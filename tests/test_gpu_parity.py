@@ -414,6 +414,57 @@ def test_identify_and_merge_beyond_the_short_sequence_paths(rule):
     _check_merge(K, V, "f16", o, *res, f"long {rule}")
 
 
+def test_identify_with_similarities_carried_over_the_decode_steps():
+    """Sets for a growing sequence with the similarities kept from call to call: a full call at
+    n0 tokens, then per new token one new similarity (kvm_sim_append) and a call that trusts the
+    buffer.  Every step must give the maps of a call that scans K itself, and the last one the
+    oracle's (same fp32 scores on both sides)."""
+    n0, n1, N, dtype = 700, 716, 720, "bf16"
+    lens1 = [n1, n1 - 300]
+    _say(f"identify over decode steps {n0}..{n1} with carried similarities (second row 300 shorter)")
+    Q, K, V = _slices(28, 2, 2, lens1, N, 128, 1, dtype)
+    del Q, V
+    mass = (np.random.default_rng(11).random((2, 2, N)) ** 3 + 1e-3).astype(np.float32)
+    Kd, md = gu.to_dev(K, dtype), torch.from_numpy(mass).cuda()
+    full = kb.kvm_params_for_budget(0.5)
+    carried = kb.kvm_params_for_budget(0.5)
+    carried.sim_given = 1
+    sim = torch.full((2, 2, N), float("nan"), dtype=torch.float32, device="cuda")
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def run(params, lens, sim_buf):
+        sl = gu.lens_dev(lens)
+        sh = kb.make_shape(Kd, 1, sl)
+        cap = kb.kvm_out_capacity(sh, params)
+        o = dict(set_id=torch.full((2, 2, N), -7, **i32), set_start=torch.full((2, 2, cap + 1), -7, **i32),
+                 pivot=torch.full((2, 2, cap), -7, **i32), n_sets=torch.full((2, 2), -7, **i32),
+                 status=torch.full((2, 2), -7, **i32))
+        ws = torch.empty(max(kb.kvm_workspace_bytes(sh, params), 256), dtype=torch.uint8, device="cuda")
+        if params.sim_given:
+            kb.kvm_sim_append(sh, Kd, sim_buf)
+        kb.kvm_identify_sets(sh, params, Kd, md, o["set_id"], o["set_start"], o["pivot"], o["n_sets"], sim_buf,
+                             o["status"], ws)
+        torch.cuda.synchronize()
+        return o
+
+    run(full, [n0, n0 - 300], sim)
+    for n in range(n0 + 1, n1 + 1):
+        lens = [n, n - 300]
+        got = run(carried, lens, sim)
+        fresh_sim = torch.empty_like(sim)
+        want = run(full, lens, fresh_sim)
+        for k in want:
+            assert torch.equal(got[k], want[k]), f"n={n}: {k} differs from the call that scans K"
+        for b, nb in enumerate(lens):
+            assert torch.equal(sim[b, :, :nb], fresh_sim[b, :, :nb]), f"n={n}: carried similarities differ"
+    o = ref.identify_sets(K, mass.astype(np.float64), dtype, full.budget, full.recent_ratio, full.heavy_ratio,
+                          full.threshold, True, got["set_start"].shape[2] - 1, lens1)
+    g = {k: v.cpu().numpy() for k, v in got.items()}
+    g["sim"] = sim.cpu().numpy()
+    exc, _ = gu.compare_maps(g, o, lens1, N, full.threshold, "carried similarities")
+    assert exc == 0
+
+
 # ---------------------------------------------------------------------------------------------
 # (c) Gaussian-kernel merge
 # ---------------------------------------------------------------------------------------------
