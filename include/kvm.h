@@ -238,6 +238,8 @@ kvm_status kvm_sim_append(const kvm_shape *shape, const void *K, float *sim, voi
  *   pivot        out  (B, H_kv, capacity) int32: absolute position; -1 for s >= M
  *   n_sets       out  (B, H_kv) int32: M (may exceed capacity: KVM_SLICE_TRUNCATED)
  *   sim_opt      out  (B, H_kv, N) float32 or NULL; sim[0] and padding are 0
+ *                     (in, entries below n_b, and not written, when params->sim_given is set;
+ *                     K is then not read and may be NULL)
  *   slice_status out  (B, H_kv) int32: KVM_SLICE_* bits
  * capacity = kvm_out_capacity().  Sets are numbered in sequence order, so the
  * compacted cache stays position-ordered.  Integer outputs are deterministic.
