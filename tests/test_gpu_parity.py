@@ -887,3 +887,71 @@ def test_whole_pass_on_a_side_stream_and_replayed_from_a_graph(rule):
         # unrelated work of the program between the replays
         other = gu.gpu_mass(inputs[which][0], inputs[which][1], dtype)
         assert np.isfinite(other).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# addressing: tensors of more than 2^32 elements
+# ---------------------------------------------------------------------------------------------
+
+def test_every_stage_on_tensors_of_more_than_2_pow_32_elements():
+    """260 x 32 slices of 4096 tokens: Q, K and V hold 4.36e9 elements each, slice (256, 0)
+    starts at element 2^32 exactly.  The bulk is a small generated block repeated on the
+    device; five slices around that boundary and at both ends carry data of their own and
+    are compared with the oracle, each stage fed the same inputs on both sides."""
+    N, d, H, B, dtype = 4096, 128, 32, 260, "f16"
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs 60 GiB of free device memory")
+    _say("stages on 260 x 32 x 4096 x 128 tensors (offsets past 2^32 elements)")
+    base = _slices(51, 2, H, [N, N], N, d, 1, dtype)
+    Qd, Kd, Vd = (gu.to_dev(x, dtype).repeat(B // 2, 1, 1, 1) for x in base)
+    assert Kd.numel() > 2 ** 32 and Kd.is_contiguous()
+    sample = [(0, 0), (255, H - 1), (256, 0), (256, 1), (B - 1, H - 1)]
+    S = len(sample)
+    Qu, Ku, Vu = _slices(52, S, 1, [N] * S, N, d, 1, dtype)                 # (S, 1, N, d) each
+    rng = np.random.default_rng(53)
+    mass_base = (rng.random((2, H, N)) ** 3 + 1e-3).astype(np.float32)
+    mass_u = (rng.random((S, 1, N)) ** 3 + 1e-3).astype(np.float32)
+    mass_in = torch.from_numpy(mass_base).cuda().repeat(B // 2, 1, 1)
+    for i, (b, h) in enumerate(sample):
+        Qd[b, h], Kd[b, h], Vd[b, h] = (gu.to_dev(x[i, 0], dtype) for x in (Qu, Ku, Vu))
+        mass_in[b, h] = torch.from_numpy(mass_u[i, 0]).cuda()
+    params = kb.kvm_params_for_budget(0.5)
+    shape = kb.make_shape(Kd, 1, None)
+    buf = kb.Buffers(shape, params, "cuda", torch.float16, with_debug=True)
+
+    # (a) aggregated scores
+    kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
+    torch.cuda.synchronize()
+    want = ref.attn_mass(Qu, Ku, dtype)
+    got = np.stack([buf.mass[b, h].cpu().numpy() for b, h in sample])[:, None]
+    err = gu.assert_mass_close(got, want, None, N, "large tensors")
+    _say(f"  mass: worst relative error {err:.2e}")
+    # (b), (c) on scores given to both sides
+    kb.kvm_identify_sets(shape, params, Kd, mass_in, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, buf.sim,
+                         buf.status, buf.ws)
+    kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.w, buf.ws)
+    torch.cuda.synchronize()
+    o = ref.identify_sets(Ku, mass_u.astype(np.float64), dtype, params.budget, params.recent_ratio, params.heavy_ratio,
+                          params.threshold, True, buf.cap)
+    rk, rv, rw = ref.merge(Ku, Vu, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
+                           bool(params.value_scale_by_set_size), None, weights=params.weights)
+    pick = lambda t: np.stack([t[b, h].cpu().numpy() for b, h in sample])[:, None]
+    g = dict(set_id=pick(buf.set_id), set_start=pick(buf.set_start), pivot=pick(buf.pivot),
+             n_sets=np.array([[int(buf.n_sets[b, h])] for b, h in sample]),
+             status=np.array([[int(buf.status[b, h])] for b, h in sample]), sim=pick(buf.sim), cap_rows=buf.cap)
+    np.testing.assert_allclose(g["sim"], o["sim"], atol=2e-6)
+    exc, near = gu.compare_maps(g, o, None, N, params.threshold, "large tensors")
+    _say(f"  maps: {exc} excused slices, {near} near-threshold similarities")
+    assert exc == 0
+    ko = np.stack([gu.to_host_f64(buf.K_out[b, h]) for b, h in sample])[:, None]
+    vo = np.stack([gu.to_host_f64(buf.V_out[b, h]) for b, h in sample])[:, None]
+    _check_merge(Ku, Vu, dtype, o, ko, vo, pick(buf.w), rk, rv, rw, None, None, "large tensors")
+    # the repeated bulk: every copy of a block slice must give the bits of the first copy
+    for b, h in ((2, 5), (258, 5), (257, H - 1)):
+        b0 = b % 2
+        if (b, h) in sample or (b0, h) in sample:
+            continue
+        assert torch.equal(buf.mass[b, h], buf.mass[b0, h]) and torch.equal(buf.set_id[b, h], buf.set_id[b0, h])
+        m = int(buf.n_sets[b0, h])
+        assert torch.equal(buf.K_out[b, h, :m], buf.K_out[b0, h, :m]) and torch.equal(buf.V_out[b, h, :m], buf.V_out[b0, h, :m])
