@@ -947,11 +947,45 @@ def test_every_stage_on_tensors_of_more_than_2_pow_32_elements():
     ko = np.stack([gu.to_host_f64(buf.K_out[b, h]) for b, h in sample])[:, None]
     vo = np.stack([gu.to_host_f64(buf.V_out[b, h]) for b, h in sample])[:, None]
     _check_merge(Ku, Vu, dtype, o, ko, vo, pick(buf.w), rk, rv, rw, None, None, "large tensors")
+    # eviction by score: kept positions and rows, bit for bit (reuses the merge's output buffers)
+    buf.K_out.zero_(), buf.V_out.zero_()
+    kb.kvm_evict(shape, params, Kd, Vd, mass_in, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.ws)
+    torch.cuda.synchronize()
+    ek, en, eko, evo = ref.evict(Ku, Vu, mass_u.astype(np.float64), dtype, params.budget, params.recent_ratio, buf.cap, None)
+    for i, (b, h) in enumerate(sample):
+        m = int(en[i, 0])
+        assert int(buf.n_sets[b, h]) == m and np.array_equal(buf.pivot[b, h].cpu().numpy(), ek[i, 0])
+        assert np.array_equal(gu.to_host_f64(buf.K_out[b, h, :m]), eko[i, 0, :m])
+        assert np.array_equal(gu.to_host_f64(buf.V_out[b, h, :m]), evo[i, 0, :m])
+    # decode-time calls: one more query row on the given scores, one similarity
+    q_new = Qd[:, :, N - 1].contiguous()
+    kept_before = buf.mass.clone()                                           # the scores of stage (a)
+    work = mass_in.clone()
+    kb.kvm_attn_mass_append(shape, q_new, Kd, work, buf.ws)
+    sim2 = torch.full_like(buf.sim, float("nan"))
+    kb.kvm_sim_append(shape, Kd, sim2)
+    torch.cuda.synchronize()
+    want = ref.attn_mass_append(np.ascontiguousarray(Qu[:, :, N - 1]), Ku, mass_u.astype(np.float64), dtype)
+    for i, (b, h) in enumerate(sample):
+        rel = np.abs(work[b, h].cpu().numpy() - want[i, 0]) / want[i, 0]
+        assert rel.max() <= gu.TOL, f"append on slice ({b},{h}): {rel.max():.2e}"
+        assert float(sim2[b, h, N - 1]) == float(buf.sim[b, h, N - 1]) and bool(torch.isnan(sim2[b, h, :N - 1]).all())
+    # the column pass alone, on row statistics from the oracle
+    lse = torch.zeros((B, H, N), dtype=torch.float32, device="cuda")
+    lse_u = ref.row_lse(Qu, Ku, dtype).astype(np.float32)
+    for i, (b, h) in enumerate(sample):
+        lse[b, h] = torch.from_numpy(lse_u[i, 0]).cuda()
+    kb.kvm_attn_mass_from_lse(shape, Qd, Kd, lse, buf.mass, buf.ws)
+    torch.cuda.synchronize()
+    for i, (b, h) in enumerate(sample):
+        assert torch.allclose(buf.mass[b, h], kept_before[b, h], rtol=1e-4, atol=0), f"from row statistics, slice ({b},{h})"
+    buf.mass.copy_(kept_before)
     # the repeated bulk: every copy of a block slice must give the bits of the first copy
     for b, h in ((2, 5), (258, 5), (257, H - 1)):
         b0 = b % 2
         if (b, h) in sample or (b0, h) in sample:
             continue
         assert torch.equal(buf.mass[b, h], buf.mass[b0, h]) and torch.equal(buf.set_id[b, h], buf.set_id[b0, h])
-        m = int(buf.n_sets[b0, h])
+        m = int(buf.n_sets[b0, h])                                           # by now the kept rows of the eviction
+        assert int(buf.n_sets[b, h]) == m
         assert torch.equal(buf.K_out[b, h, :m], buf.K_out[b0, h, :m]) and torch.equal(buf.V_out[b, h, :m], buf.V_out[b0, h, :m])
