@@ -122,6 +122,35 @@ def test_mass_large_scores_do_not_overflow():
     assert (np.abs(got - want)[big] / want[big]).max() <= gu.TOL
 
 
+@pytest.mark.parametrize("dtype,n", [("f16", 100000), ("bf16", 70001), ("f32", 20000)])
+def test_mass_long_sequence_against_a_closed_form(dtype, n):
+    """Too long for the oracle's n^2 loop, so the scores are given a shape whose column sums have
+    a closed form at any length: every query is beta e_1, hence row t is a softmax of the same
+    numbers c alpha_j (alpha_j = first component of key j) cut off at j <= t, and
+    mass_j = exp(c alpha_j) * sum over t >= j of 1 / (sum over i <= t of exp(c alpha_i)).
+    Head 1 has zero queries: harmonic numbers.  The other components of the keys are noise."""
+    _say(f"mass: closed form at n={n}, {dtype}")
+    rng = np.random.default_rng(19)
+    beta = 8.0
+    k = rng.standard_normal((1, 2, n, 128)).astype(np.float32)
+    q = np.zeros((1, 2, n, 128), np.float32)
+    q[0, 0, :, 0] = beta
+    K, Q = synth.to_storage(k, dtype), synth.to_storage(q, dtype)
+    alpha = synth.to_f64(K[0, 0], dtype)[:, 0]                # as stored
+    e = np.exp(beta / math.sqrt(128.0) * alpha)
+    tail = np.cumsum((1.0 / np.cumsum(e))[::-1])[::-1]        # sum over t >= j of 1 / Z_t
+    Hn = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    want = np.stack([e * tail, Hn[n] - Hn[:n]])[None]
+    got = gu.gpu_mass(Q, K, dtype)
+    err = gu.assert_mass_close(got, want, None, n, f"closed form n={n}")
+    _say(f"  worst relative error {err:.2e}")
+    # one decode step on top: the same closed form one token further, from the library's own scores
+    if n > 1:
+        short = gu.gpu_mass(Q, K, dtype, seq_lens=[n - 1])
+        again = gu.gpu_mass_append(np.ascontiguousarray(Q[:, :, n - 1]), K, short, dtype, seq_lens=[n])
+        gu.assert_mass_close(again, want, None, n, f"closed form n={n}, last row appended")
+
+
 @pytest.mark.parametrize("dtype,G,lens,N", [("f16", 1, [600], 600), ("bf16", 4, [300, 129, 0, 1, 256], 320),
                                             ("f32", 2, [257, 64], 257), ("f16", 1, [2100, 1500], 2100)])
 def test_mass_from_row_statistics_of_the_caller(dtype, G, lens, N):
