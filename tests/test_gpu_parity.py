@@ -122,7 +122,7 @@ def test_mass_large_scores_do_not_overflow():
     assert (np.abs(got - want)[big] / want[big]).max() <= gu.TOL
 
 
-@pytest.mark.parametrize("dtype,n", [("f16", 100000), ("bf16", 70001), ("f32", 20000)])
+@pytest.mark.parametrize("dtype,n", [("f16", 100000), ("bf16", 70001), ("f32", 20000), ("f16", 2 ** 22)])
 def test_mass_long_sequence_against_a_closed_form(dtype, n):
     """Too long for the oracle's n^2 loop, so the scores are given a shape whose column sums have
     a closed form at any length: every query is beta e_1, hence row t is a softmax of the same
@@ -132,20 +132,22 @@ def test_mass_long_sequence_against_a_closed_form(dtype, n):
     _say(f"mass: closed form at n={n}, {dtype}")
     rng = np.random.default_rng(19)
     beta = 8.0
-    k = rng.standard_normal((1, 2, n, 128)).astype(np.float32)
-    q = np.zeros((1, 2, n, 128), np.float32)
+    heads = 1 if n > 10 ** 6 else 2                          # the longest case: one head, no decode step (time)
+    k = rng.standard_normal((1, heads, n, 128), dtype=np.float32)
+    q = np.zeros((1, heads, n, 128), np.float32)
     q[0, 0, :, 0] = beta
     K, Q = synth.to_storage(k, dtype), synth.to_storage(q, dtype)
-    alpha = synth.to_f64(K[0, 0], dtype)[:, 0]                # as stored
+    del k, q
+    alpha = synth.to_f64(np.ascontiguousarray(K[0, 0, :, 0]), dtype)   # as stored
     e = np.exp(beta / math.sqrt(128.0) * alpha)
     tail = np.cumsum((1.0 / np.cumsum(e))[::-1])[::-1]        # sum over t >= j of 1 / Z_t
     Hn = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
-    want = np.stack([e * tail, Hn[n] - Hn[:n]])[None]
+    want = np.stack([e * tail, Hn[n] - Hn[:n]][:heads])[None]
     got = gu.gpu_mass(Q, K, dtype)
     err = gu.assert_mass_close(got, want, None, n, f"closed form n={n}")
     _say(f"  worst relative error {err:.2e}")
     # one decode step on top: the same closed form one token further, from the library's own scores
-    if n > 1:
+    if heads == 2:
         short = gu.gpu_mass(Q, K, dtype, seq_lens=[n - 1])
         again = gu.gpu_mass_append(np.ascontiguousarray(Q[:, :, n - 1]), K, short, dtype, seq_lens=[n])
         gu.assert_mass_close(again, want, None, n, f"closed form n={n}, last row appended")
@@ -414,6 +416,34 @@ def test_identify_infeasible_budget_is_reported():
     gu.compare_maps(g, o, None, n, params.threshold, "infeasible")
     want = kb.KVM_SLICE_FALLBACK | kb.KVM_SLICE_INFEASIBLE | kb.KVM_SLICE_TRUNCATED
     assert g["status"][0, 0] == want and g["n_sets"][0, 0] > g["cap_rows"]
+
+
+def test_identify_and_merge_at_the_maximum_length():
+    """One slice of 2^22 tokens, the longest sequence the library accepts (one more is refused)."""
+    n, dtype = 2 ** 22, "f16"
+    _say(f"identify + merge at N={n}")
+    rng = np.random.default_rng(29)
+    # keys that share a direction for a stretch and then jump (mean stretch 32 tokens): within a
+    # stretch adjacent keys have cosine similarity near 0.9, across a jump near 0
+    noise = rng.standard_normal((n, 128), dtype=np.float32)
+    stretch = np.cumsum(rng.random(n) < 1 / 32)
+    direction = rng.standard_normal((int(stretch[-1]) + 1, 128), dtype=np.float32)
+    k = np.float32(math.sqrt(0.9)) * direction[stretch] + np.float32(math.sqrt(0.1)) * noise
+    del noise, direction
+    K = synth.to_storage(k[None, None], dtype)
+    V = synth.to_storage(rng.standard_normal((1, 1, n, 128), dtype=np.float32), dtype)
+    del k
+    mass = rng.random((1, 1, n)) ** 3 + 1e-3
+    params = kb.kvm_params_for_budget(0.5)
+    g, o = _identify_both(K, mass, dtype, params)
+    np.testing.assert_allclose(g["sim"], o["sim"], atol=2e-6)
+    exc, near = gu.compare_maps(g, o, None, n, params.threshold, "maximum length")
+    _say(f"  sets {int(o['n_sets'][0, 0])}, excused slices {exc}, near-threshold similarities {near}")
+    gu.check_partition(g, None, n, g["cap_rows"])
+    res = _merge_both(K, V, dtype, params, o)
+    _check_merge(K, V, dtype, o, *res, "maximum length")
+    sh = kb.KvmShape(1, 1, 1, n + 1, 128, kb.KVM_F16, None)
+    assert kb.kvm_workspace_bytes(sh, params) == 0 and b"too large" in kb.load_library().kvm_last_error()
 
 
 @pytest.mark.parametrize("rule", ["adjacent", "anchor"])
