@@ -8,6 +8,7 @@ of the exact value up to 2e-5 of the row maximum; singleton sets bit-identical. 
 inputs (mass rounded to fp32, index maps), never outputs of the HIP path.
 """
 import math
+import os
 import sys
 
 import numpy as np
@@ -795,6 +796,27 @@ def test_whole_pass_config2_full_size_sampled():
     tot = mass.double().sum(-1).cpu().numpy()
     assert np.abs(tot / N - 1).max() <= 1e-5, f"scores of a slice do not sum to n: {np.abs(tot / N - 1).max():.2e}"
     assert (mass[:, :, 0] >= 1).all() and (mass[:, :, N - 1] <= 1).all() and (mass > 0).all()
+
+
+_OPT_IN = pytest.mark.skipif(os.environ.get("KVM_FULL_SIZE_TESTS") != "1",
+                             reason="generates 48 GiB of inputs (about a minute); set KVM_FULL_SIZE_TESTS=1 to run")
+
+
+@pytest.mark.parametrize("cfg_id,budget", [(3, 0.35), (4, 0.5), pytest.param(5, 0.35, marks=_OPT_IN)])
+def test_whole_pass_large_configs_full_size_sampled(cfg_id, budget):
+    """The three large workloads whole, as the benchmark launches them; the oracle on one slice of
+    every length from the last layer (the highest addresses), partition properties on all slices.
+    The largest one is left to an explicit request because of the 48 GiB of host memory it takes."""
+    cfg = synth.CONFIGS[cfg_id]
+    _say(f"whole pass: config {cfg_id} at full size")
+    Q, K, V, lens = synth.gen_config(cfg)
+    B, H = K.shape[0], cfg["H_kv"]
+    per = cfg["batch"]
+    sample = [(B - per + i, (7 * i + 3) % H) for i in range(per)] + [(0, 0)]
+    g = _whole_pass(Q, K, V, cfg["dtype"], cfg["G"], kb.kvm_params_for_budget(budget), lens, sample,
+                    f"config {cfg_id} full")
+    n_b = np.full(B, cfg["N"]) if lens is None else np.asarray(lens)
+    assert (g["n_sets"] <= np.floor(budget * n_b)[:, None]).all() and (g["n_sets"] > 0).all()
 
 
 @pytest.mark.parametrize("variant", ["average_last", "gaussian_random", "fixed_sigma", "anchor_sets"])
