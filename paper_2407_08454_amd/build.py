@@ -32,5 +32,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+MICROBENCH_SRC = os.path.join(_PKG, "microbench", "ceilings.hip")
+MICROBENCH_BIN = os.path.join(_PKG, "microbench", "ceilings")
+
+
+def build_microbench(verbose: bool = False) -> str:
+    """The stand-alone program that measures what plain kernels reach on the box (see its header)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", MICROBENCH_SRC, "-o", MICROBENCH_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    return MICROBENCH_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
