@@ -7,7 +7,9 @@
 //      difference is the chip's power limit at work);
 //   2. the attention step built up piece by piece: fragments from LDS (each read feeding two
 //      MFMAs), plus the softmax arithmetic of one score (fma, exp2, add), plus the per-step
-//      barrier and the asynchronous tile load -- three workgroups of four waves per CU;
+//      barrier and the asynchronous tile load, plus tiles that really come from memory -- three
+//      workgroups of four waves per CU, as the library's kernels run; and two other shapes of
+//      the same step that move fewer tile bytes per MFMA;
 //   3. issue cost of v_fma_f32, v_exp_f32 and the softmax triple;
 //   4. HBM: a read-only and a copy kernel over 1 GiB.
 //
@@ -60,21 +62,26 @@ __global__ __launch_bounds__(256) void mfma_stream(float *out, const u32x4 *src,
 
 // ---- 2. the attention step, piece by piece -----------------------------------------------------
 // PIECES bit 0: softmax arithmetic on every accumulator; bit 1: barrier + asynchronous tile load
-// per step.  A "step" is a 64-row tile against the wave's two stationary 32-row blocks:
-// 4 blocks of 8 MFMAs, 16 fragment reads of 16 bytes per lane.
-template <int PIECES>
-__global__ __launch_bounds__(256, 3) void attention_step(float *out, const u32x4 *src, int steps, float c)
+// per step.  A "step" is a 64-row tile against the wave's R stationary 32-row blocks: 2 R blocks
+// of 8 MFMAs, 16 fragment reads of 16 bytes per lane.  WAVES waves share the tile; WGS workgroups
+// per CU.  With `stream` the tiles come from a large buffer instead of a cache-hot one, `share`
+// workgroups of an XCD walking through the same tiles (as the workgroups of one slice do).
+template <int PIECES, int WAVES, int WGS, int R>
+__global__ __launch_bounds__(64 * WAVES, WGS) void attention_step(float *out, const u32x4 *src, int steps, float c,
+                                                                   const u32x4 *stream, size_t stream_tiles, int share)
 {
     __shared__ u32x4 tile[2][1024];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = threadIdx.x; i < 2048; i += 256) (&tile[0][0])[i] = src[i & 1023];
+    for (int i = threadIdx.x; i < 2048; i += 64 * WAVES) (&tile[0][0])[i] = src[i & 1023];
     __syncthreads();
-    u32x4 stat[2][8];
-    for (int r = 0; r < 2; ++r)
+    u32x4 stat[R][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
         for (int f = 0; f < 8; ++f) stat[r][f] = src[(lane * 16 + r * 8 + f + wave) & 1023];
     float l0 = 0.f, l1 = 0.f;
     const float m = 0.25f;
-    const u32x4 *g = src + (blockIdx.x & 7) * 64;
+    const size_t group = ((size_t)(blockIdx.x >> 3) / share) * 8 + (blockIdx.x & 7);
     for (int s = 0; s < steps; ++s) {
         const u32x4 *cur = tile[s & 1];
         if (PIECES & 2) {
@@ -82,10 +89,10 @@ __global__ __launch_bounds__(256, 3) void attention_step(float *out, const u32x4
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                __builtin_amdgcn_global_load_lds((gptr_t)(g + ((wave * 4 + i) * 64 + lane) % 512),
-                                                 (lptr_t)(&tile[(s + 1) & 1][(wave * 4 + i) * 64]), 16, 0, 0);
+            // the 16 chunks of 64 slots of the next tile, dealt out to the waves
+            const u32x4 *g = stream ? stream + ((group * steps + s) % stream_tiles) * 1024 : src;
+            for (int ch = wave; ch < 16; ch += WAVES)
+                __builtin_amdgcn_global_load_lds((gptr_t)(g + ch * 64 + lane), (lptr_t)(&tile[(s + 1) & 1][ch * 64]), 16, 0, 0);
         }
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
@@ -93,7 +100,7 @@ __global__ __launch_bounds__(256, 3) void attention_step(float *out, const u32x4
 #pragma unroll
             for (int f = 0; f < 8; ++f) a[f] = cur[(32 * blk + (lane & 31)) * 16 + ((2 * f + (lane >> 5)) ^ (lane & 15))];
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
+            for (int r = 0; r < R; ++r) {
                 f32x16 acc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -221,18 +228,35 @@ int main()
         std::printf("   %-16s %8.3f ms   %6.0f TFLOP/s\n", which ? "random operands" : "zero operands", ms, flops / (ms * 1e-3) / 1e12);
     }
 
-    std::printf("2. attention step model, 3 workgroups of 4 waves per CU, random operands\n");
+    std::printf("2. attention step model (random operands unless said otherwise)\n");
     {
         const int steps = 4000;
-        const double flops = (double)SIMDS * 3 * steps * 32 * MFMA_FLOPS;
-        float ms = time_ms([&] { hipLaunchKernelGGL((attention_step<0>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f); }, 3);
-        std::printf("   %-44s %8.3f ms   %6.0f TFLOP/s\n", "fragments from LDS", ms, flops / (ms * 1e-3) / 1e12);
-        ms = time_ms([&] { hipLaunchKernelGGL((attention_step<1>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f); }, 3);
-        std::printf("   %-44s %8.3f ms   %6.0f TFLOP/s\n", "+ fma, exp2, add per score", ms, flops / (ms * 1e-3) / 1e12);
-        ms = time_ms([&] { hipLaunchKernelGGL((attention_step<3>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f); }, 3);
-        std::printf("   %-44s %8.3f ms   %6.0f TFLOP/s\n", "+ barrier and asynchronous tile load", ms, flops / (ms * 1e-3) / 1e12);
-        ms = time_ms([&] { hipLaunchKernelGGL((attention_step<3>), dim3(CUS * 3), dim3(256), 0, 0, out, zero, steps, 0.01f); }, 3);
-        std::printf("   %-44s %8.3f ms   %6.0f TFLOP/s\n", "the same on zero operands", ms, flops / (ms * 1e-3) / 1e12);
+        const size_t stream_tiles = 65536;                   // 1 GiB of 16 KB tiles holding the random pattern
+        u32x4 *big;
+        CHECK(hipMalloc(&big, stream_tiles * 16384));
+        for (size_t t = 0; t < stream_tiles; ++t) CHECK(hipMemcpyAsync(big + t * 1024, rnd, 16384, hipMemcpyDeviceToDevice, 0));
+        CHECK(hipDeviceSynchronize());
+        auto report = [&](const char *name, float ms, double mfma_per_simd) {
+            std::printf("   %-66s %8.3f ms   %6.0f TFLOP/s\n", name, ms, (double)SIMDS * mfma_per_simd * MFMA_FLOPS / (ms * 1e-3) / 1e12);
+        };
+        const u32x4 *none = nullptr;
+        const double base = 3.0 * steps * 32;                // three waves per SIMD, 32 MFMAs per wave and step
+        report("4-wave workgroups, 3 per CU: fragments from LDS",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<0, 4, 3, 2>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f, none, 1, 8); }, 3), base);
+        report("  + fma, exp2, add per score",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<1, 4, 3, 2>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f, none, 1, 8); }, 3), base);
+        report("  + barrier and asynchronous tile load (cache-hot tile)",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<3, 4, 3, 2>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f, none, 1, 8); }, 3), base);
+        report("  the same on zero operands",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<3, 4, 3, 2>), dim3(CUS * 3), dim3(256), 0, 0, out, zero, steps, 0.01f, none, 1, 8); }, 3), base);
+        report("  + tiles streamed from a 1 GiB buffer, 8 workgroups per stream",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<3, 4, 3, 2>), dim3(CUS * 3), dim3(256), 0, 0, out, rnd, steps, 0.01f, (const u32x4 *)big, stream_tiles, 8); }, 3), base);
+        report("12-wave workgroups, 1 per CU: streamed tiles, 3 workgroups per stream",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<3, 12, 1, 2>), dim3(CUS), dim3(768), 0, 0, out, rnd, steps, 0.01f, (const u32x4 *)big, stream_tiles, 3); }, 3), base);
+        report("4 stationary blocks, 4-wave workgroups, 2 per CU: streamed tiles, 4 per stream",
+               time_ms([&] { hipLaunchKernelGGL((attention_step<3, 4, 2, 4>), dim3(CUS * 2), dim3(256), 0, 0, out, rnd, steps / 2, 0.01f, (const u32x4 *)big, stream_tiles, 4); }, 3),
+               2.0 * (steps / 2) * 64);
+        CHECK(hipFree(big));
     }
 
     std::printf("3. VALU issue, 8 waves per SIMD, 16 independent chains per lane\n");
