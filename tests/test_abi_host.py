@@ -28,6 +28,30 @@ def test_library_exports_every_declared_symbol():
     assert re.fullmatch(r"\d+\.\d+\.\d+", lib.kvm_version().decode())
 
 
+def test_header_is_plain_c_and_matches_the_binding_structs(tmp_path):
+    """The header has to compile as C99 and as C++ on its own, and the ctypes mirror of its two
+    structs has to have the sizes and field offsets the C compiler gives them."""
+    import subprocess
+    fields = {"kvm_shape": [f[0] for f in kb.KvmShape._fields_], "kvm_params": [f[0] for f in kb.KvmParams._fields_]}
+    lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "kvm.h"', 'int main(void) {']
+    for st, names in fields.items():
+        lines.append(f'  printf("{st} %zu\\n", sizeof({st}));')
+        for n in names:
+            lines.append(f'  printf("{st}.{n} %zu\\n", offsetof({st}, {n}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)], check=True)
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for st, cls in (("kvm_shape", kb.KvmShape), ("kvm_params", kb.KvmParams)):
+        assert int(got[st]) == ctypes.sizeof(cls)
+        for n in fields[st]:
+            assert int(got[f"{st}.{n}"]) == getattr(cls, n).offset, f"{st}.{n}"
+
+
 def test_presets_follow_the_printed_hyperparameters():
     p = kb.kvm_params_for_budget(0.5)
     assert (p.budget, p.recent_ratio, p.heavy_ratio, p.threshold) == (0.5, 0.17, 0.12, 0.75)
