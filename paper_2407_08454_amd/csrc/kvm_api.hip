@@ -327,7 +327,7 @@ kvm_status kvm_profile_enable(int32_t max_launches)
     g_prof.names = new const char *[max_launches];
     for (int i = 0; i < 2 * max_launches; ++i) {
         if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
-            g_prof.cap = i / 2;
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);   // cap is still 0: disable frees the arrays only
             kvm_profile_disable();
             set_error("kvm_profile_enable: hipEventCreate failed");
             return KVM_ERR_LAUNCH;
