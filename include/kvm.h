@@ -275,6 +275,28 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
                      void *K_out, void *V_out, float *w_opt, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * kvm_merge for callers that cannot allocate device memory or may not call an allocator
+ * where they run: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as kvm_merge, without the workspace: the
+ * work plan (one int32 per 64-token tile of every slice, plus one per slice) is kept in a
+ * buffer built into the library, KVM_MERGE_STATIC_MAX_PLAN_ENTRIES int32 (8 MiB) on every
+ * GPU the library has run this call on, held until the process ends.  The call allocates
+ * nothing and frees nothing.
+ *   - B * H_kv * (ceil(N / 64) + 1) > KVM_MERGE_STATIC_MAX_PLAN_ENTRIES returns
+ *     KVM_ERR_WORKSPACE before any launch (use kvm_merge with a workspace then).
+ *   - The buffer belongs to the device that is current at the call (the device the tensors
+ *     live on); its address is looked up on the first call on that device.
+ *   - All calls on one GPU share the one buffer: two calls whose kernels may overlap on
+ *     that GPU (different streams, different threads) race on it.  Calls on one stream,
+ *     one after the other, are safe; the buffer keeps the last call's plan and needs no
+ *     clearing, since every entry that is read is written by the same call first.
+ */
+#define KVM_MERGE_STATIC_MAX_PLAN_ENTRIES (1 << 21)
+kvm_status kvm_merge_static(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                            const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,
+                            void *K_out, void *V_out, float *w_opt, void *stream);
+
+/*
  * Comparison workload, not part of the method: eviction by aggregated attention score, the
  * selection policy of the heavy-hitter methods the paper measures itself against (Section 2.3;
  * Section 4.2 compares average weighted merging with it at the same budget).  Per slice it

@@ -25,7 +25,7 @@ KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
            "kvm_attn_mass_from_lse", "kvm_attn_mass_append", "kvm_sim_append",
-           "kvm_identify_sets", "kvm_merge", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
+           "kvm_identify_sets", "kvm_merge", "kvm_merge_static", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
 _TORCH_DTYPE = {torch.float32: KVM_F32, torch.float16: KVM_F16, torch.bfloat16: KVM_BF16}
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_merge.restype = ctypes.c_int
+    lib.kvm_merge_static.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9
+    lib.kvm_merge_static.restype = ctypes.c_int
     lib.kvm_evict.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 8 + [S, P]
     lib.kvm_evict.restype = ctypes.c_int
     lib.kvm_profile_enable.argtypes = [ctypes.c_int32]
@@ -239,7 +241,7 @@ def kvm_identify_sets(shape: KvmShape, params: KvmParams, K, mass, set_id, set_s
         _ptr(n_sets), _ptr(sim_opt), _ptr(slice_status), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
-def kvm_merge(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, ws):
+def _check_merge_operands(shape, params, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, ws=None):
     _same_device(K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, ws)
     B, H, N, d = shape.B, shape.H_kv, shape.N, shape.d
     cap = kvm_out_capacity(shape, params)
@@ -258,10 +260,22 @@ def kvm_merge(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets
         raise ValueError("dtype mismatch")
     if w_opt is not None and w_opt.dtype != torch.float32:
         raise ValueError("w_opt must be float32")
+
+
+def kvm_merge(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, ws):
+    _check_merge_operands(shape, params, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, ws)
     _check("kvm_merge", load_library().kvm_merge(
         ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(set_start), _ptr(pivot), _ptr(n_sets),
         _ptr(K_out), _ptr(V_out), _ptr(w_opt), None if ws is None else _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_merge_static(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt):
+    """kvm_merge without a workspace: the work plan lives in a buffer built into the library."""
+    _check_merge_operands(shape, params, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt)
+    _check("kvm_merge_static", load_library().kvm_merge_static(
+        ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(set_start), _ptr(pivot), _ptr(n_sets),
+        _ptr(K_out), _ptr(V_out), _ptr(w_opt), _stream()))
 
 
 def kvm_evict(shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_out, V_out, ws):

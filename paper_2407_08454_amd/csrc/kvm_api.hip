@@ -305,6 +305,23 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
                         (hipStream_t)stream);
 }
 
+kvm_status kvm_merge_static(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                            const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out, void *V_out,
+                            float *w_opt, void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_merge_static");
+    if (rc != KVM_OK) return rc;
+    rc = check_params(params, "kvm_merge_static");
+    if (rc != KVM_OK) return rc;
+    const int cap = capacity(shape, params);
+    if ((long long)shape->B * shape->N == 0 || cap == 0) return KVM_OK;
+    if (!K || !V || !set_start || !pivot || !n_sets || !K_out || !V_out) {
+        set_error("kvm_merge_static: a required pointer is NULL");
+        return KVM_ERR_INVALID_ARG;
+    }
+    return launch_merge_static(*shape, *params, cap, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, (hipStream_t)stream);
+}
+
 kvm_status kvm_profile_disable(void)
 {
     if (g_prof.ev) {

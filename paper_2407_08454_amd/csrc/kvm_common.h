@@ -193,6 +193,9 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
 kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
                         void *V_out, float *w_opt, int32_t *plan, hipStream_t st);
+kvm_status launch_merge_static(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
+                               const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
+                               void *V_out, float *w_opt, hipStream_t st);
 kvm_status launch_evict(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, uint8_t *flags,
                         hipStream_t st);

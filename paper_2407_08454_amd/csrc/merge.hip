@@ -11,6 +11,8 @@
 // fp32, then one rounded row is written per output.  Loads are issued 16 rows at a time; a
 // set of up to 16 tokens is read exactly once and held in registers.  Runs of singleton sets
 // are copied bit for bit.  HBM traffic: K once, V once, 2 M rows out.
+#include <mutex>
+
 #include "kvm_common.h"
 
 namespace kvm {
@@ -302,6 +304,60 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     default: launch_merge_t<bf16_t>(sh, K, V, K_out, V_out, a, st); break;
     }
     return check_launch("merge_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
+// The merge for callers that cannot allocate: the work plan goes into a file-scope device
+// array instead of a caller-supplied workspace.  Every GPU the library runs on holds its own
+// copy of the array at its own address; the address is looked up once per device, with that
+// device current, and host code only ever uses the looked-up pointer.
+// ------------------------------------------------------------------------------------------
+
+constexpr size_t STATIC_PLAN_INTS = (size_t)KVM_MERGE_STATIC_MAX_PLAN_ENTRIES;
+static __device__ __align__(256) int32_t scratch[STATIC_PLAN_INTS];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static int32_t *g_scratch_ptr[STATIC_MAX_DEVICES];           // per device; nullptr = not looked up yet
+
+static kvm_status static_plan_ptr(int32_t **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) {
+        set_error("kvm_merge_static: no usable current device (%s)", e != hipSuccess ? hipGetErrorString(e) : "index out of range");
+        return KVM_ERR_LAUNCH;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error("kvm_merge_static: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+            return KVM_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = static_cast<int32_t *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return KVM_OK;
+}
+
+kvm_status launch_merge_static(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
+                               const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
+                               void *V_out, float *w_opt, hipStream_t st)
+{
+    const size_t need = merge_workspace_bytes(sh) / sizeof(int32_t);
+    if (need > STATIC_PLAN_INTS) {
+        set_error("kvm_merge_static: the work plan needs %zu entries (B*H_kv*(ceil(N/64)+1)), the built-in buffer holds %zu; "
+                  "use kvm_merge with a workspace", need, STATIC_PLAN_INTS);
+        return KVM_ERR_WORKSPACE;
+    }
+    int32_t *plan = nullptr;
+    kvm_status rc = static_plan_ptr(&plan);
+    if (rc != KVM_OK) return rc;
+    // every plan entry a merge wave reads is written by the plan kernel of the same call (or
+    // clamped when the maps are inconsistent), so nothing has to be cleared between calls
+    return launch_merge(sh, pr, cap_rows, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, plan, st);
 }
 
 }  // namespace kvm

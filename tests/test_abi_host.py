@@ -148,6 +148,16 @@ def test_host_detectable_errors_return_before_any_launch():
     assert merge(_shape(), p, ws=None) == kb.KVM_ERR_WORKSPACE
     assert merge(_shape(), p, nbytes=4) == kb.KVM_ERR_WORKSPACE
 
+    def merge_static(sh, pr, K=one):
+        return lib.kvm_merge_static(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, one, None, None)
+
+    assert merge_static(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
+    assert merge_static(_shape(d=256), p) == kb.KVM_ERR_UNSUPPORTED
+    assert merge_static(_shape(N=0), p, K=None) == kb.KVM_OK                      # nothing to do
+    # 2^16 slices of 2049 plan entries each do not fit the built-in buffer of 2^21: refused, nothing launched
+    assert merge_static(_shape(B=2 ** 10, H_kv=2 ** 6, N=2 ** 17), p) == kb.KVM_ERR_WORKSPACE
+    assert b"built-in buffer" in lib.kvm_last_error()
+
 
 def test_binding_refuses_mismatched_tensors_on_the_host():
     import torch
