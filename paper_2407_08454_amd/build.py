@@ -8,7 +8,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_PKG), "include")
 LIB_PATH = os.path.join(_PKG, "libkvm.so")
-SOURCES = ["kvm_api.hip", "attn_mass.hip", "attn_append.hip", "identify.hip", "merge.hip"]
+SOURCES = ["kvm_api.hip", "attn_mass.hip", "attn_pipe.hip", "attn_append.hip", "identify.hip", "merge.hip"]
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     # packed fp32 VALU forms are switched off for every kernel of this library

@@ -20,160 +20,9 @@
 // and by power, not by the matrix pipe: at d = 128 a 32x32 block costs 8 MFMAs (256 cycles) and
 // at least 48 VALU instructions (one fma, one exp2, one add per score), and packed fp32
 // arithmetic is not used.  Hence the attention to every VALU instruction in the block loops.
-#include "kvm_common.h"
+#include "attn_tile.h"
 
 namespace kvm {
-
-constexpr int ATT_BLOCK = 256;           // 4 waves
-constexpr int ATT_WAVES = ATT_BLOCK / WAVE;
-
-template <typename T> struct Mma;
-
-template <> struct Mma<half_t> {
-    static constexpr int CHUNKS = 16;    // 16-byte chunks per 128-element row
-    static constexpr int FRAGS = 8;      // 16-byte fragments a lane holds per 32-row block
-    static constexpr int NBLK = 2;       // 32-row blocks per streamed tile and per wave's stationary operand
-    static __device__ __forceinline__ void mma(f32x16 &acc, const u32x4 &a, const u32x4 &b) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
-    }
-};
-
-template <> struct Mma<bf16_t> {
-    static constexpr int CHUNKS = 16;
-    static constexpr int FRAGS = 8;
-    static constexpr int NBLK = 2;
-    static __device__ __forceinline__ void mma(f32x16 &acc, const u32x4 &a, const u32x4 &b) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-    }
-};
-
-template <> struct Mma<float> {
-    static constexpr int CHUNKS = 32;
-    static constexpr int FRAGS = 16;
-    static constexpr int NBLK = 1;
-    static __device__ __forceinline__ void mma(f32x16 &acc, const u32x4 &a, const u32x4 &b) {
-        // (the elements are copied out first: a bit cast applied directly to a vector
-        // element lvalue reads element 0 with this compiler)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t ai = a[i], bi = b[i];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, ai), __builtin_bit_cast(float, bi), acc, 0, 0, 0);
-        }
-    }
-};
-
-// In a 32x32 MFMA result, accumulator i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32.
-__device__ __forceinline__ int acc_row(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
-
-// A streamed tile in LDS: TR rows of CHUNKS 16-byte chunks; chunk ch of row r sits at
-// position ch ^ (r mod CHUNKS), so that 16 lanes reading one chunk column of 16
-// consecutive rows hit 16 different bank groups.
-typedef const __attribute__((address_space(1))) void *gptr_t;
-typedef __attribute__((address_space(3))) void *lptr_t;
-
-constexpr int ATT_MIN_BLOCKS = 3;        // workgroups per CU the register budget is held to (3 waves per SIMD)
-
-// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters at max)
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for
-// every outstanding global_load_lds, i.e. for the tiles that are meant to stay in flight.
-// The LDS data a step needs is waited for explicitly with wait_vmcnt before the barrier.
-__device__ __forceinline__ void barrier_no_fence() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
-template <typename T> struct Tile {
-    static constexpr int CH = Mma<T>::CHUNKS;
-    static constexpr int TR = 32 * Mma<T>::NBLK;
-    static constexpr int SLOTS = TR * CH;                     // 16-byte slots per stage
-    static constexpr int PER_THREAD = SLOTS / ATT_BLOCK;      // global_load_lds instructions per wave and tile
-    static __device__ __forceinline__ int lds_index(int row, int ch) { return row * CH + (ch ^ (row & (CH - 1))); }
-
-    // Rows [row0, row0+TR) of an (N x 128) matrix -> one LDS stage, asynchronously.  One
-    // instruction fills 64 consecutive slots (lane l -> slot base + l), so the swizzle is
-    // applied on the source side: the lane that fills slot (row, pos) fetches chunk
-    // pos ^ (row mod CH).  The byte offsets of a lane's loads relative to the first row of
-    // the tile do not depend on the tile: they are computed once, and a full tile is then
-    // fetched with a scalar base address and no per-lane arithmetic.
-    struct Offsets { uint32_t v[PER_THREAD]; };
-    static __device__ __forceinline__ Offsets offsets(int wave, int lane) {
-        Offsets o;
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int slot0 = (wave * PER_THREAD + i) * 64;
-            const int row = slot0 / CH + lane / CH;
-            const int pos = lane % CH;
-            o.v[i] = (uint32_t)(row * (HEAD_DIM * (int)sizeof(T)) + ((pos ^ (row & (CH - 1))) * 16));
-        }
-        return o;
-    }
-    // the same offsets for a ragged tile with only rows_valid (1 <= rows_valid < TR) rows:
-    // rows past the end are replaced by the last valid row (finite data whose scores are
-    // masked or weighted by zero later), so that nothing outside the matrix is read
-    static __device__ __forceinline__ Offsets offsets_clamped(int wave, int lane, int rows_valid) {
-        Offsets o;
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int slot0 = (wave * PER_THREAD + i) * 64;
-            const int row = slot0 / CH + lane / CH;
-            const int pos = lane % CH;
-            o.v[i] = (uint32_t)(min(row, rows_valid - 1) * (HEAD_DIM * (int)sizeof(T)) + ((pos ^ (row & (CH - 1))) * 16));
-        }
-        return o;
-    }
-    // Rows [row0, row0+TR) of the matrix whose row 0 is at `base`, clamped to n_valid rows.  The
-    // tile's first row goes through readfirstlane so that it stays in scalar registers and the
-    // loads take the (scalar base + 32-bit lane offset) form.
-    static __device__ __forceinline__ void issue(const T *base, int row0, int n_valid, const Offsets &full, u32x4 *stage,
-                                                 int wave, int lane) {
-        Offsets o = full;
-        if (row0 + TR > n_valid) o = offsets_clamped(wave, lane, n_valid - row0);
-        const uint64_t u = reinterpret_cast<uint64_t>(base + (size_t)row0 * HEAD_DIM);
-        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
-        const char *first_row = reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(first_row + o.v[i]), (lptr_t)(stage + (wave * PER_THREAD + i) * 64), 16, 0, 0);
-    }
-    // fragment f of 32-row block blk for this lane (MFMA A operand)
-    static __device__ __forceinline__ u32x4 frag(const u32x4 *lds, int blk, int f, int lane) {
-        return lds[lds_index(32 * blk + (lane & 31), 2 * f + (lane >> 5))];
-    }
-};
-
-// The stationary operand: rows [row0, row0+32) straight from global memory into registers.
-template <typename T>
-__device__ __forceinline__ void load_stationary(const T *base, int row0, int n_valid, int lane, u32x4 *frags) {
-    const int row = row0 + (lane & 31);
-#pragma unroll
-    for (int f = 0; f < Mma<T>::FRAGS; ++f) {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (row < n_valid)
-            v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base + (size_t)row * HEAD_DIM) + (2 * f + (lane >> 5)) * 16);
-        frags[f] = v;
-    }
-}
-
-// blockIdx -> (slice, tile).  Workgroups are dealt round-robin to the 8 XCDs, each with its
-// own L2: all tiles of a slice go to one XCD so that the slice's K and Q are fetched once.
-// Within a slice the tiles with the most causal work come first.
-struct TileMap {
-    int slice, tile;
-    bool valid;
-};
-__device__ __forceinline__ TileMap map_block(int n_slices, int tiles_per_slice) {
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    TileMap m;
-    m.slice = (idx / tiles_per_slice) * 8 + xcd;
-    m.tile = idx % tiles_per_slice;
-    m.valid = m.slice < n_slices;
-    return m;
-}
 
 // ------------------------------------------------------------------------------------------
 // per-block reductions
@@ -184,15 +33,6 @@ __device__ __forceinline__ TileMap map_block(int n_slices, int tiles_per_slice) 
 // one accumulator block at a time, the eight fragments of a block fetched together, and the
 // overlap of MFMA, exp2 and LDS traffic is left to the hardware interleaving the waves.
 // ------------------------------------------------------------------------------------------
-
-__device__ __forceinline__ float max16(const f32x16 &v) {
-    const float a = fmaxf(fmaxf(v[0], v[1]), v[2]), b = fmaxf(fmaxf(v[3], v[4]), v[5]);
-    const float c = fmaxf(fmaxf(v[6], v[7]), v[8]), d = fmaxf(fmaxf(v[9], v[10]), v[11]);
-    const float e = fmaxf(fmaxf(v[12], v[13]), v[14]);
-    return fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), fmaxf(e, v[15]));
-}
-
-constexpr float M_INIT = -3.0e38f;       // "no score seen yet": finite, so that no inf - inf arises
 
 // pass 1: the online (max, sum) of a row absorbs 16 more scores (-inf = masked)
 __device__ __forceinline__ void rowstat_update(const f32x16 &acc, float c, float &m_run, float &l_run) {
@@ -263,24 +103,6 @@ __device__ __forceinline__ f32x16 score_block(const u32x4 *tile, int blk, const 
     return acc;
 }
 
-// Unmasked tiles (16-bit types): the 8 A fragments of a 32-row block are fetched once, all
-// reads in flight together, and serve both stationary blocks of the wave.
-// The slot of fragment f of a lane within a 32-row block does not depend on the block or the
-// stage; the eight slots are computed once and the block and stage become constant offsets.
-struct FragSlots { int v[8]; };
-template <typename T>
-__device__ __forceinline__ FragSlots frag_slots(int lane) {
-    FragSlots s;
-#pragma unroll
-    for (int f = 0; f < 8; ++f) s.v[f] = Tile<T>::lds_index(lane & 31, 2 * f + (lane >> 5));
-    return s;
-}
-template <typename T>
-__device__ __forceinline__ void load_frags8(const u32x4 *tile, int blk, const FragSlots &s, u32x4 *a) {
-#pragma unroll
-    for (int f = 0; f < 8; ++f) a[f] = tile[s.v[f] + 32 * Tile<T>::CH * blk];
-}
-
 template <typename T>
 __device__ __forceinline__ f32x16 score_block8(const u32x4 *a, const u32x4 *bfrag) {
     f32x16 acc;
@@ -295,18 +117,6 @@ __device__ __forceinline__ f32x16 score_block8(const u32x4 *a, const u32x4 *bfra
 // pass 1: row log-sum-exp
 // ------------------------------------------------------------------------------------------
 
-// accumulator i of lane l: is its row index inside the 32x32 block above / below the lane's column?
-__device__ __forceinline__ void mask_rows_above_col(f32x16 &acc, int lane) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-        if (acc_row(i, lane) > (lane & 31)) acc[i] = -INFINITY;
-}
-__device__ __forceinline__ void mask_rows_below_col(f32x16 &acc, int lane) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-        if (acc_row(i, lane) < (lane & 31)) acc[i] = -INFINITY;
-}
-
 // HOLD (16-bit types only): the running maximum is taken from key tile 0 and held for the tiles
 // below the diagonal, which saves the maximum and the rescaling of every block; the diagonal
 // tile updates it again.  Should a later score exceed the held maximum by so much that a term
@@ -318,7 +128,8 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
                                                                  float *__restrict__ lse, int32_t *__restrict__ redo,
                                                                  const int32_t *__restrict__ seq_lens,
                                                                  int n_qslices, int HG, int G, int N, int n_pad,
-                                                                 int tiles_per_slice, int wgs_per_slice, float c)
+                                                                 int tiles_per_slice, int wgs_per_slice, float c,
+                                                                 float out_scale, float pad)
 {
     using M = Mma<T>;
     using TL = Tile<T>;
@@ -459,22 +270,24 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
         if (s + 1 < steps) step(s + 1, lds_b, lds_a);
     }
     wait_vmcnt<0>();                                          // no load may still target this workgroup's LDS
-    if constexpr (HOLD) {
-        bool finite = true;
-#pragma unroll
-        for (int qb = 0; qb < NB; ++qb) finite = finite && l_run[qb] <= 3.0e38f;   // false for +inf and NaN
-        const int bad = __syncthreads_or(finite ? 0 : 1);
-        if (threadIdx.x == 0) redo[(size_t)qslice * tiles_per_slice + tile] = bad;
-    }
-    // lanes l and l+32 hold the two halves of a row's keys; rows in [n, n_pad) get +inf so
-    // that the second pass weighs them with exp2(-inf) = 0
+    // lanes l and l+32 hold the two halves of a row's keys.  The statistic is stored as
+    // out_scale * L_t; rows in [n, n_pad) get `pad`, the infinity whose sign makes the second pass
+    // weigh them with exp2(-inf) = 0.
+    bool finite = true;
 #pragma unroll
     for (int qb = 0; qb < NB; ++qb) {
         const float m_o = __shfl_xor(m_run[qb], 32, WAVE), l_o = __shfl_xor(l_run[qb], 32, WAVE);
         const float m = fmaxf(m_run[qb], m_o);
         const float l = l_run[qb] * __builtin_amdgcn_exp2f((m_run[qb] - m) * c) + l_o * __builtin_amdgcn_exp2f((m_o - m) * c);
+        const float L = m * c + __log2f(l);
         const int q = q0 + 32 * qb + (lane & 31);
-        if (lane < 32 && q < n_pad) lse[(size_t)qslice * n_pad + q] = q < n ? m * c + __log2f(l) : INFINITY;
+        // (checked on the combined sum: two finite halves can still add up to infinity)
+        if (q < n) finite = finite && fabsf(L) <= 3.0e38f;    // false for infinities and NaN
+        if (lane < 32 && q < n_pad) lse[(size_t)qslice * n_pad + q] = q < n ? L * out_scale : pad;
+    }
+    if constexpr (HOLD) {
+        const int bad = __syncthreads_or(finite ? 0 : 1);
+        if (threadIdx.x == 0) redo[(size_t)qslice * tiles_per_slice + tile] = bad;
     }
     barrier_no_fence();                                       // everybody is done with LDS before the next tile's loads
     }
@@ -644,19 +457,28 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
 int attn_lse_stride(int N);
 
 // Row statistics handed in by the caller: natural-log sums, one per query row, without padding.
-// They are copied into the padded base-2 layout that the column-sum kernel streams; rows past
-// the slice's length get +inf, which makes their terms vanish.
+// They are copied into the padded layout that the column-sum kernel streams (scale = log2(e): L_t
+// in base 2, or -sqrt(d): -L_t / c for attn_colsum_pipe_kernel); rows past the slice's length get
+// the infinity that makes their terms vanish.
 __global__ void __launch_bounds__(256) lse_import_kernel(const float *__restrict__ row_lse, float *__restrict__ lse,
                                                          const int32_t *__restrict__ seq_lens, int HG, int N, int n_pad,
-                                                         int blocks_per_slice)
+                                                         int blocks_per_slice, float scale, float pad)
 {
     const int qslice = blockIdx.x / blocks_per_slice;
     const int q = (blockIdx.x % blocks_per_slice) * 256 + threadIdx.x;
     if (q >= n_pad) return;
     int n = seq_lens ? seq_lens[qslice / HG] : N;
     n = n < 0 ? 0 : (n > N ? N : n);
-    lse[(size_t)qslice * n_pad + q] = q < n ? row_lse[(size_t)qslice * N + q] * 1.44269504088896341f : INFINITY;
+    lse[(size_t)qslice * n_pad + q] = q < n ? row_lse[(size_t)qslice * N + q] * scale : pad;
 }
+
+void launch_colsum_pipe(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass, int n_pad, float c,
+                        hipStream_t st);
+
+// From this length on the column sums of 16-bit inputs are taken by attn_colsum_pipe_kernel
+// (attn_pipe.hip): measured 5 % faster at N = 16384, 1-3 % slower at N = 4096, where the eight
+// diagonal steps of its 512-key workgroups weigh more.
+constexpr int COLSUM_PIPE_MIN_N = 8192;
 
 template <typename T>
 static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass, float *lse,
@@ -667,11 +489,14 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, co
     const float c = (float)(1.4426950408889634 / sqrt((double)sh.d));
     const int n_q = sh.B * sh.H_kv * sh.G, n_kv = sh.B * sh.H_kv;
     const int n_pad = attn_lse_stride(sh.N);
+    const bool pipe = Mma<T>::NBLK == 2 && sh.N >= COLSUM_PIPE_MIN_N;
+    // how the row statistic is stored for the second pass: L_t, or -L_t / c for attn_colsum_pipe_kernel
+    const float out_scale = pipe ? -1.f / c : 1.f, pad = pipe ? -INFINITY : INFINITY;
     if (row_lse) {
         ProfScope prof("lse_import_kernel", st);
         const int per = (n_pad + 255) / 256;
         hipLaunchKernelGGL(lse_import_kernel, dim3((unsigned)((long long)per * n_q)), dim3(256), 0, st, row_lse, lse,
-                           sh.seq_lens, sh.H_kv * sh.G, sh.N, n_pad, per);
+                           sh.seq_lens, sh.H_kv * sh.G, sh.N, n_pad, per, 1.44269504088896341f * out_scale, pad);
         kvm_status rc = check_launch("lse_import_kernel");
         if (rc != KVM_OK) return rc;
     } else {
@@ -685,19 +510,20 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, co
             {
                 ProfScope prof("attn_lse_kernel", st);
                 hipLaunchKernelGGL((attn_lse_kernel<T, true>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
-                                   (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c);
+                                   (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad, tiles, wgs, c,
+                                   out_scale, pad);
             }
             kvm_status rc = check_launch("attn_lse_kernel");
             if (rc != KVM_OK) return rc;
             ProfScope prof("attn_lse_redo_kernel", st);
             hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)((n_q + 7) / 8 * 8)), dim3(ATT_BLOCK), 0, st,
                                (const T *)Q, (const T *)K, lse, redo, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad,
-                               tiles, 1, c);
+                               tiles, 1, c, out_scale, pad);
         } else {
             ProfScope prof("attn_lse_kernel", st);
             hipLaunchKernelGGL((attn_lse_kernel<T, false>), dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
                                (const T *)K, lse, (int32_t *)nullptr, sh.seq_lens, n_q, sh.H_kv * sh.G, sh.G, sh.N, n_pad,
-                               tiles, wgs, c);
+                               tiles, wgs, c, out_scale, pad);
         }
         kvm_status rc = check_launch("attn_lse_kernel");
         if (rc != KVM_OK) return rc;
@@ -706,7 +532,8 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, co
         const int wgs = tiles >= 8 ? (tiles + 1) / 2 : tiles;   // as for the row statistics
         const long long blocks = (long long)((n_kv + 7) / 8) * 8 * wgs;
         ProfScope prof("attn_colsum_kernel", st);
-        hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
+        if (pipe) launch_colsum_pipe(sh, Q, K, lse, mass, n_pad, c, st);
+        else hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
                            (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, wgs, c);
         return check_launch("attn_colsum_kernel");
     }

@@ -181,6 +181,36 @@ def gen_config(cfg: dict, layers: int | None = None, layer_offset: int = 0, work
     return Q, K, V, sl
 
 
+def gen_config_layers(cfg: dict, workers: int | None = None):
+    """The same tensors one layer at a time (for workloads too large to hold on the host at once):
+    yields (Q, K, V, seq_lens) of layer 0, 1, ..., each with the bits gen_config gives that layer.
+    One pool of spawned worker processes serves all layers."""
+    B, H, G, N, d, sl = config_dims(cfg, 1)
+    npdt = storage_numpy_dtype(cfg["dtype"])
+    total = B * H
+    lens_all = [N if sl is None else int(sl[bh // H]) for bh in range(total)]
+    if workers is None:
+        workers = min(16, os.cpu_count() or 1)
+    chunk = max(1, min(8, (64 * 4096) // max(N, 1)))
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    with ProcessPoolExecutor(max_workers=max(workers, 1), mp_context=mp.get_context("spawn")) as ex:
+        for layer in range(cfg["layers"]):
+            base = layer * total
+            jobs = [(cfg["seed"], base + f, min(chunk, total - f), lens_all[f:f + chunk], d, G, cfg["rho"],
+                     cfg["dtype"], N) for f in range(0, total, chunk)]
+            Q = np.empty((B, H * G, N, d), dtype=npdt)
+            K = np.empty((B, H, N, d), dtype=npdt)
+            V = np.empty((B, H, N, d), dtype=npdt)
+            for j, res in zip(jobs, ex.map(_gen_chunk, jobs)):
+                for i, (q, k, v) in enumerate(res):
+                    b, h = divmod(j[1] - base + i, H)
+                    Q[b, h * G:(h + 1) * G] = q
+                    K[b, h] = k
+                    V[b, h] = v
+            yield Q, K, V, sl
+
+
 def slice_of(Q, K, V, b: int, h: int, G: int):
     """Views of one slice out of full tensors: Q (G, N, d), K (N, d), V (N, d)."""
     return Q[b, h * G:(h + 1) * G], K[b, h], V[b, h]

@@ -671,27 +671,63 @@ def test_merge_tolerates_inconsistent_maps():
 # whole pass
 # ---------------------------------------------------------------------------------------------
 
-def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
+def _explained_by_near_ties_in_mass(m_o, oi, og, ge, n, what):
+    """The library's maps (equal to the oracle's rule on the library's own scores, checked before)
+    differ from the oracle's maps on the oracle's scores: the first decision that went the other
+    way has to be one between scores that the two sides agree on to within the tolerance of the
+    scores themselves.  Conserved sets first (the exact top-k); if they agree the sets agree and
+    only pivots can differ."""
+    m = m_o[0, 0, :n]
+    P_o, P_g = oi["protected"][0, 0, :n].astype(bool), og["protected"][0, 0, :n].astype(bool)
+    if not np.array_equal(P_o, P_g):
+        n_rec = int(P_o[::-1].argmin()) if not P_o.all() else n       # length of the trailing conserved window
+        heavy = np.flatnonzero(P_o[:n - n_rec])
+        assert len(heavy), f"{what}: conserved tokens differ without a top-k selection"
+        T = m[heavy].min()                                            # the smallest selected score
+        odd = np.flatnonzero(P_o != P_g)
+        worst = np.abs(m[odd] / T - 1).max()
+        assert worst <= 2.5 * gu.TOL, f"{what}: conserved tokens differ at scores {worst:.2e} away from the k-th largest"
+        return "top-k near-tie"
+    assert np.array_equal(ge["set_id"][0, 0, :n], oi["set_id"][0, 0, :n]), f"{what}: same conserved tokens, different sets"
+    M = min(int(oi["n_sets"][0, 0]), oi["cap_rows"])
+    pg, po = ge["pivot"][0, 0, :M], oi["pivot"][0, 0, :M]
+    odd = np.flatnonzero(pg != po)
+    assert len(odd), f"{what}: maps differ but neither conserved tokens, sets nor pivots do"
+    worst = np.abs(m[pg[odd]] / m[po[odd]] - 1).max()
+    assert worst <= 2.5 * gu.TOL, f"{what}: pivots differ between scores {worst:.2e} apart"
+    return "pivot near-tie"
+
+
+def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what, device_tensors=None, slice_of=None):
     """GPU: the three calls back to back on all slices.  Oracle: the same on sampled slices.
-    Stage by stage the oracle's inputs are its own; the end-to-end maps are compared too and
-    slices whose maps differ (a near-tie in independently computed mass) are counted."""
-    Qd, Kd, Vd = gu.to_dev(Q, dtype), gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+    Stage by stage the oracle's inputs are its own.  End to end the library's maps must be exactly
+    what the oracle's rule gives on the library's own fp32 scores (themselves checked against the
+    oracle's scores first), the only excuse being a similarity within 1e-6 of the threshold; where
+    they differ from the oracle's maps on the oracle's scores the deciding scores must be a near-tie.
+    With device_tensors = (Qd, Kd, Vd) the inputs are already on the GPU and slice_of(b, h) returns
+    the host copy (Q (G, N, d), K (N, d), V (N, d)) of a sampled slice."""
+    if device_tensors is None:
+        Qd, Kd, Vd = gu.to_dev(Q, dtype), gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+        slice_of = lambda b, h: (Q[b, h * G:(h + 1) * G], K[b, h], V[b, h])
+    else:
+        Qd, Kd, Vd = device_tensors
     sl = gu.lens_dev(lens)
     sh = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(sh, params, "cuda", gu.TORCH_DT[dtype], with_debug=True)
     kb.compress(sh, params, Qd, Kd, Vd, buf)
     torch.cuda.synchronize()
-    B, H, N, d = K.shape
+    B, H, N, d = Kd.shape
     g = dict(set_id=buf.set_id.cpu().numpy(), set_start=buf.set_start.cpu().numpy(), pivot=buf.pivot.cpu().numpy(),
              n_sets=buf.n_sets.cpu().numpy(), status=buf.status.cpu().numpy(), sim=buf.sim.cpu().numpy())
     gu.check_partition(g, lens, N, buf.cap, what)
     mass_g = buf.mass.cpu().numpy()
-    differing = 0
+    differing = excused = 0
     for (b, h) in sample:
         n = N if lens is None else int(lens[b])
         _say(f"  {what}: oracle on slice ({b},{h}) n={n}")
-        Qs = np.ascontiguousarray(Q[b:b + 1, h * G:(h + 1) * G])
-        Ks, Vs = np.ascontiguousarray(K[b:b + 1, h:h + 1]), np.ascontiguousarray(V[b:b + 1, h:h + 1])
+        q_s, k_s, v_s = slice_of(b, h)
+        Qs = np.ascontiguousarray(q_s)[None]
+        Ks, Vs = np.ascontiguousarray(k_s)[None, None], np.ascontiguousarray(v_s)[None, None]
         ls = None if lens is None else [n]
         if G > 1:      # the query heads in parallel: the grouped score is the sum of the heads' scores
             m_o = ref.attn_mass(Qs.transpose(1, 0, 2, 3).copy(), np.repeat(Ks, G, 0), dtype,
@@ -702,25 +738,33 @@ def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
         # stage (b) and (c) on the oracle's own fp32-rounded mass
         m32 = m_o.astype(np.float32)
         gi = gu.gpu_identify(Ks, m32, dtype, params, ls)
-        oi = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
-                               params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"], ls,
-                               pivot_rule=params.pivot_rule, pivot_seed=params.pivot_seed, set_rule=params.set_rule)
-        if params.set_rule == kb.KVM_SETS_ANCHOR:
+        ident = lambda mass64, seed: ref.identify_sets(
+            Ks, mass64, dtype, params.budget, params.recent_ratio, params.heavy_ratio, params.threshold,
+            bool(params.enforce_budget), gi["cap_rows"], ls, pivot_rule=params.pivot_rule, pivot_seed=seed,
+            set_rule=params.set_rule)
+        oi = ident(m32.astype(np.float64), params.pivot_seed)
+        anchor = params.set_rule == kb.KVM_SETS_ANCHOR
+        if anchor:
             _compare_anchor_maps(gi, oi, f"{what} ({b},{h})")
         else:
             gu.compare_maps(gi, oi, ls, N, params.threshold, f"{what} ({b},{h})")
         res = _merge_both(Ks, Vs, dtype, params, oi, ls)
         _check_merge(Ks, Vs, dtype, oi, *res, f"{what} ({b},{h})")
-        # end to end: GPU maps from GPU mass against oracle maps from oracle mass
-        oe = oi
-        if params.pivot_rule == kb.KVM_PIVOT_RANDOM:         # the draws depend on the slice's index in the call
-            oe = ref.identify_sets(Ks, m32.astype(np.float64), dtype, params.budget, params.recent_ratio,
-                                   params.heavy_ratio, params.threshold, bool(params.enforce_budget), gi["cap_rows"],
-                                   ls, pivot_rule=params.pivot_rule, set_rule=params.set_rule,
-                                   pivot_seed=(params.pivot_seed + ((b * H + h) << 32)) % (1 << 64))
-        same = all(np.array_equal(g[k][b, h], oe[k][0, 0]) for k in ("set_id", "set_start", "pivot"))
+        # end to end.  The draws of the random pivot depend on the slice's index in the call.
+        seed_here = (params.pivot_seed + ((b * H + h) << 32)) % (1 << 64)
+        ge = {k: g[k][b:b + 1, h:h + 1] for k in ("set_id", "set_start", "pivot", "n_sets", "status")}
+        ge["cap_rows"] = buf.cap
+        # (i) the oracle's rule on the library's own scores: bit-exact, similarities at the threshold excused
+        og = ident(mass_g[b:b + 1, h:h + 1].astype(np.float64), seed_here)
+        if anchor:
+            excused += _compare_anchor_maps(ge, og, f"{what} ({b},{h}) on the library's scores")
+        else:
+            excused += gu.compare_maps(ge, og, ls, N, params.threshold, f"{what} ({b},{h}) on the library's scores")[0]
+        # (ii) against the oracle's maps on the oracle's scores
+        oe = oi if params.pivot_rule != kb.KVM_PIVOT_RANDOM else ident(m32.astype(np.float64), seed_here)
+        same = all(np.array_equal(ge[k][0, 0], oe[k][0, 0]) for k in ("set_id", "set_start", "pivot"))
         if same:
-            M = min(int(oi["n_sets"][0, 0]), buf.cap)
+            M = min(int(oe["n_sets"][0, 0]), buf.cap)
             rk, rv = res[3], res[4]
             if oe is not oi:
                 rk, rv, _ = ref.merge(Ks, Vs, dtype, oe["set_start"], oe["pivot"], oe["n_sets"], params.sigma_mode,
@@ -731,8 +775,14 @@ def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what):
                 f"{what} ({b},{h}): end-to-end K/V error {ek:.2e}/{ev:.2e}"
         else:
             differing += 1
-    _say(f"  {what}: {differing} of {len(sample)} sampled slices have end-to-end maps that differ (mass near-ties)")
-    assert differing <= max(1, len(sample) // 4)
+            near_sim = np.abs(oe["sim"][0, 0, 1:n] - params.threshold).min() <= gu.NEAR if n > 1 else False
+            if anchor:
+                near_sim = oe["anchor_margin"][0, 0] <= gu.NEAR
+            why = "similarity at the threshold" if near_sim else \
+                _explained_by_near_ties_in_mass(m_o, oe, og, ge, n, f"{what} ({b},{h})")
+            _say(f"  {what} ({b},{h}): end-to-end maps differ from the oracle's on its own scores: {why}")
+    _say(f"  {what}: {differing} of {len(sample)} sampled slices have end-to-end maps that differ "
+         f"(each explained by a near-tie); {excused} excused by a similarity at the threshold")
     return g
 
 
@@ -798,15 +848,10 @@ def test_whole_pass_config2_full_size_sampled():
     assert (mass[:, :, 0] >= 1).all() and (mass[:, :, N - 1] <= 1).all() and (mass > 0).all()
 
 
-_OPT_IN = pytest.mark.skipif(os.environ.get("KVM_FULL_SIZE_TESTS") != "1",
-                             reason="generates 48 GiB of inputs (about a minute); set KVM_FULL_SIZE_TESTS=1 to run")
-
-
-@pytest.mark.parametrize("cfg_id,budget", [(3, 0.35), (4, 0.5), pytest.param(5, 0.35, marks=_OPT_IN)])
+@pytest.mark.parametrize("cfg_id,budget", [(3, 0.35), (4, 0.5)])
 def test_whole_pass_large_configs_full_size_sampled(cfg_id, budget):
-    """The three large workloads whole, as the benchmark launches them; the oracle on one slice of
-    every length from the last layer (the highest addresses), partition properties on all slices.
-    The largest one is left to an explicit request because of the 48 GiB of host memory it takes."""
+    """Workloads 3 and 4 whole, as the benchmark launches them; the oracle on one slice of every
+    length from the last layer (the highest addresses), partition properties on all slices."""
     cfg = synth.CONFIGS[cfg_id]
     _say(f"whole pass: config {cfg_id} at full size")
     Q, K, V, lens = synth.gen_config(cfg)
@@ -817,6 +862,40 @@ def test_whole_pass_large_configs_full_size_sampled(cfg_id, budget):
                     f"config {cfg_id} full")
     n_b = np.full(B, cfg["N"]) if lens is None else np.asarray(lens)
     assert (g["n_sets"] <= np.floor(budget * n_b)[:, None]).all() and (g["n_sets"] > 0).all()
+
+
+def test_whole_pass_config5_full_size_sampled():
+    """Workload 5 whole (4 x 32 x 32 slices padded to 16384 tokens, 16 GiB per tensor, offsets
+    beyond 2^32 together with per-sequence lengths), in the launch the benchmark times.  The
+    inputs are generated and copied to the GPU one layer at a time, so the host never holds more
+    than one layer; the host copies of the sampled slices (one of every length from the last layer,
+    one from the first) are kept for the oracle."""
+    cfg = synth.CONFIGS[5]
+    budget = 0.35
+    L, per, H, G, N, d, dtype = cfg["layers"], cfg["batch"], cfg["H_kv"], cfg["G"], cfg["N"], cfg["d"], cfg["dtype"]
+    B = L * per
+    _say("whole pass: config 5 at full size, filled layer by layer")
+    tdt = gu.TORCH_DT[dtype]
+    Qd = torch.empty((B, H * G, N, d), dtype=tdt, device="cuda")
+    Kd = torch.empty((B, H, N, d), dtype=tdt, device="cuda")
+    Vd = torch.empty((B, H, N, d), dtype=tdt, device="cuda")
+    sample = [(B - per + i, (7 * i + 3) % H) for i in range(per)] + [(0, 0)]
+    kept = {}
+    lens = None
+    for layer, (Q, K, V, sl) in enumerate(synth.gen_config_layers(cfg)):
+        b0 = layer * per
+        Qd[b0:b0 + per].copy_(gu.to_dev(Q, dtype))
+        Kd[b0:b0 + per].copy_(gu.to_dev(K, dtype))
+        Vd[b0:b0 + per].copy_(gu.to_dev(V, dtype))
+        for (b, h) in sample:
+            if b0 <= b < b0 + per:
+                kept[(b, h)] = (Q[b - b0, h * G:(h + 1) * G].copy(), K[b - b0, h].copy(), V[b - b0, h].copy())
+        lens = sl if lens is None else np.concatenate([lens, sl])
+        if layer % 8 == 7:
+            _say(f"  {layer + 1} of {L} layers on the GPU")
+    g = _whole_pass(None, None, None, dtype, G, kb.kvm_params_for_budget(budget), lens, sample, "config 5 full",
+                    device_tensors=(Qd, Kd, Vd), slice_of=lambda b, h: kept[(b, h)])
+    assert (g["n_sets"] <= np.floor(budget * np.asarray(lens))[:, None]).all() and (g["n_sets"] > 0).all()
 
 
 @pytest.mark.parametrize("variant", ["average_last", "gaussian_random", "fixed_sigma", "anchor_sets"])
