@@ -328,7 +328,8 @@ kvm_status kvm_evict(const kvm_shape *shape, const kvm_params *params, const voi
  *       record per kernel name (at most max), returns the number of records,
  *       and clears the recording so that it can be filled again.
  *   kvm_profile_disable()             destroys the events.
- * Not thread-safe: enable, launch and collect from one thread.
+ * Not thread-safe: enable, launch and collect from one thread.  Launches on a stream that is
+ * being captured into a HIP graph are not timed (nothing is recorded into the graph).
  */
 typedef struct {
     char name[48];            /* kernel name, e.g. "attn_colsum_kernel"          */

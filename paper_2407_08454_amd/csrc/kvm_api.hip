@@ -43,6 +43,10 @@ static ProfState g_prof;
 ProfScope::ProfScope(const char *name, hipStream_t s) : slot(-1), st(s)
 {
     if (!g_prof.on || g_prof.used >= g_prof.cap) return;
+    // a stream that is being captured into a graph is not timed: the event records would become
+    // nodes of the caller's graph
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return;
     slot = g_prof.used++;
     g_prof.names[slot] = name;
     (void)hipEventRecord(g_prof.ev[2 * slot], st);

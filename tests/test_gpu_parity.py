@@ -89,8 +89,8 @@ def test_mass_scores_rising_far_above_the_first_keys(dtype):
     n = 700
     _say(f"mass: rising scores, {dtype}")
     rng = np.random.default_rng(12)
-    q = rng.standard_normal((1, 2, n, 128)).astype(np.float32)
-    k = rng.standard_normal((1, 2, n, 128)).astype(np.float32)
+    q = rng.standard_normal((1, 3, n, 128)).astype(np.float32)
+    k = rng.standard_normal((1, 3, n, 128)).astype(np.float32)
     # head 0: every query and key shares a component that grows with the position
     ramp = np.linspace(0.0, 60.0, n, dtype=np.float32)
     q[0, 0, :, 0] = 40.0
@@ -98,6 +98,11 @@ def test_mass_scores_rising_far_above_the_first_keys(dtype):
     # head 1: a single late key far above everything before it
     q[0, 1, :, 1] = 30.0
     k[0, 1, 400, 1] = 90.0
+    # head 2: all scores zero except two late keys, 127.2 to 127.6 binary orders above the rest and held
+    # by different halves of a wave: each half's sum of exponentials is finite, their sum is not
+    q[0, 2], k[0, 2] = 0.0, 0.0
+    q[0, 2, :, 2] = 30.0
+    k[0, 2, 400, 2] = k[0, 2, 404, 2] = 33.355
     Q, K = synth.to_storage(q, dtype), synth.to_storage(k, dtype)
     want = ref.attn_mass(Q, K, dtype)
     got = gu.gpu_mass(Q, K, dtype)
@@ -106,7 +111,7 @@ def test_mass_scores_rising_far_above_the_first_keys(dtype):
     # require the rest to be small
     big = want > 1e-6
     assert (np.abs(got[big] - want[big]) / want[big]).max() <= gu.TOL
-    assert np.abs(got[~big]).max() <= 2e-6 and got.sum() == pytest.approx(2 * n, rel=1e-4)
+    assert np.abs(got[~big]).max() <= 2e-6 and got.sum() == pytest.approx(3 * n, rel=1e-4)
 
 
 def test_mass_large_scores_do_not_overflow():

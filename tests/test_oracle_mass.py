@@ -31,7 +31,7 @@ def test_widening_is_exact_for_every_bit_pattern():
     bits = np.arange(65536, dtype=np.uint16)
     want16 = bits.view(np.float16).astype(np.float64)
     wantbf = synth.bf16_bits_to_f32(bits).astype(np.float64)
-    for b in list(range(0, 65536, 97)) + [0, 1, 0x03FF, 0x0400, 0x7BFF, 0x7C00, 0x8000, 0xFBFF, 0xFC00, 0x7E00]:
+    for b in range(65536):                                   # all of them: zeros, subnormals, infinities, NaNs
         got = ref.half_to_double(int(b))
         assert (math.isnan(got) and math.isnan(want16[b])) or got == want16[b]
         got = ref.bf16_to_double(int(b))
