@@ -570,6 +570,319 @@ __global__ __launch_bounds__(SEG_BLOCK) void segment_kernel(SegArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
+// segmentation of slices of up to 16384 tokens (adjacent rule): everything in registers
+// ------------------------------------------------------------------------------------------
+//
+// segment_kernel above walks a slice in tiles and goes back to memory for the scores, the
+// similarities and the flag bytes in every one of its passes; with 1024 threads per slice each of
+// its ~40 barriers is expensive and only two slices fit a CU.  Here a thread owns 16 consecutive
+// tokens and keeps their score keys, similarities and flag bits in registers from one coalesced
+// read to the final write; a workgroup has just enough threads for the slice (256 for 4096
+// tokens: four slices per CU, the whole headline workload resident at once), and the same steps
+// -- exact top-k by radix select, boundary test, budget rule, set numbering, segmented arg-max --
+// run on the registers.  Same results bit for bit.
+
+constexpr int SR_ITEMS = 16;
+
+template <int BLOCK> struct SegRegShared {
+    int hist[256];
+    int wave_i[BLOCK / WAVE];
+    int wave_i2[BLOCK / WAVE];
+    unsigned long long wave_k[BLOCK / WAVE];
+    int wave_f[BLOCK / WAVE];
+    int bc[2];
+    unsigned long long bck;
+    uint32_t bits[BLOCK + 1];            // one 16-bit mask per thread, handed to the neighbour
+};
+
+template <int WAVES>
+__device__ __forceinline__ int block_exclusive_sum_w(int v, int &total, int *wave_slots) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        int t = __shfl_up(inc, off, WAVE);
+        if (lane >= off) inc += t;
+    }
+    __syncthreads();                                         // wave_slots may still be read from a previous use
+    if (lane == WAVE - 1) wave_slots[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+        int a = wave_slots[i];
+        if (i < w) before += a;
+        all += a;
+    }
+    total = all;
+    return before + inc - v;
+}
+
+// k-th largest (k >= 1) of the keys whose bit is set in `valid` (16 keys per thread).  Needs
+// k <= number of valid keys.  Returns the key value T and the number of valid keys greater than T.
+template <int BLOCK>
+__device__ void select_kth_largest_reg(const uint32_t *key, uint32_t valid, int k, uint32_t &T, int &greater,
+                                       SegRegShared<BLOCK> &sh)
+{
+    uint32_t prefix = 0, mask = 0;
+    int remaining = k, gt = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int i = threadIdx.x; i < 256; i += BLOCK) sh.hist[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < SR_ITEMS; ++i)
+            if (((valid >> i) & 1u) && (key[i] & mask) == prefix) atomicAdd(&sh.hist[(key[i] >> shift) & 255u], 1);
+        __syncthreads();
+        if (threadIdx.x < WAVE) {
+            const int lane = threadIdx.x;
+            int h[4], s = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { h[i] = sh.hist[lane * 4 + i]; s += h[i]; }
+            int suf = s;                                     // inclusive suffix sum over lanes
+#pragma unroll
+            for (int off = 1; off < WAVE; off <<= 1) {
+                int t = __shfl_down(suf, off, WAVE);
+                if (lane + off < WAVE) suf += t;
+            }
+            int above = suf - s;                             // keys in higher-numbered lanes' bins
+#pragma unroll
+            for (int i = 3; i >= 0; --i) {
+                if (above < remaining && remaining <= above + h[i]) { sh.bc[0] = lane * 4 + i; sh.bc[1] = above; }
+                above += h[i];
+            }
+        }
+        __syncthreads();
+        const int digit = sh.bc[0], above = sh.bc[1];
+        gt += above;
+        remaining -= above;
+        prefix |= (uint32_t)digit << shift;
+        mask |= 255u << shift;
+    }
+    T = prefix;
+    greater = gt;
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void segment_reg_kernel(SegArgs a)
+{
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ SegRegShared<BLOCK> sh;
+    const int slice = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, w = tid >> 6;
+    const int n = clamp_len(a.seq_lens, slice / a.H, a.N);
+    const float *mass = a.mass + (size_t)slice * a.N;
+    const float *sim = a.sim + (size_t)slice * a.N;
+    int32_t *set_id = a.set_id + (size_t)slice * a.N;
+    int32_t *set_start = a.set_start + (size_t)slice * (a.cap_rows + 1);
+    int32_t *pivot = a.pivot + (size_t)slice * a.cap_rows;
+    const float eps = a.threshold;
+
+    int n_recent = (int)floor(a.recent_ratio * (double)n);
+    if (n_recent > n) n_recent = n;
+    int n_heavy = (int)floor(a.heavy_ratio * (double)n);
+    const int pre = n - n_recent;                            // the top-k is taken over [0, pre)
+    if (n_heavy > pre) n_heavy = pre;
+    const int cap = (int)floor(a.budget * (double)n);
+
+    // this thread's tokens jb .. jb+15: score keys and similarities, read once (16 bytes at a time
+    // where the rows are aligned for it)
+    const int jb = tid * SR_ITEMS;
+    const bool vec = (a.N & 3) == 0 && ((reinterpret_cast<uintptr_t>(a.mass) | reinterpret_cast<uintptr_t>(a.sim) |
+                                         reinterpret_cast<uintptr_t>(a.set_id)) & 15) == 0;
+    uint32_t key[SR_ITEMS];
+    float sm[SR_ITEMS];
+#pragma unroll
+    for (int v = 0; v < SR_ITEMS / 4; ++v) {
+        f32x4 m4 = {0.f, 0.f, 0.f, 0.f}, s4 = {0.f, 0.f, 0.f, 0.f};
+        if (vec && jb + 4 * v + 3 < a.N) {                   // (N is the row stride: whole vectors stay inside the row)
+            m4 = *reinterpret_cast<const f32x4 *>(mass + jb + 4 * v);
+            s4 = *reinterpret_cast<const f32x4 *>(sim + jb + 4 * v);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (jb + 4 * v + e < a.N) { m4[e] = mass[jb + 4 * v + e]; s4[e] = sim[jb + 4 * v + e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float me = m4[e];
+            key[4 * v + e] = sortable_key(me);
+            sm[4 * v + e] = s4[e];
+        }
+    }
+    uint32_t in_n = 0, in_pre = 0;                           // bit i: token jb+i < n, < pre
+#pragma unroll
+    for (int i = 0; i < SR_ITEMS; ++i) {
+        in_n |= (jb + i < n ? 1u : 0u) << i;
+        in_pre |= (jb + i < pre ? 1u : 0u) << i;
+    }
+    for (int j = n + tid; j < a.N; j += BLOCK) set_id[j] = -1;
+
+    // ---- conserved tokens: the recent window and the exact top-k of the scores before it --------
+    uint32_t prot = in_n & ~in_pre;
+    if (n_heavy > 0) {
+        uint32_t T1;
+        int gt1;
+        select_kth_largest_reg<BLOCK>(key, in_pre, n_heavy, T1, gt1, sh);
+        const int take_eq1 = n_heavy - gt1;
+        int eq_cnt = 0;
+#pragma unroll
+        for (int i = 0; i < SR_ITEMS; ++i) eq_cnt += (((in_pre >> i) & 1u) && key[i] == T1) ? 1 : 0;
+        int total;
+        int rank = block_exclusive_sum_w<WAVES>(eq_cnt, total, sh.wave_i);
+#pragma unroll
+        for (int i = 0; i < SR_ITEMS; ++i) {
+            if (!((in_pre >> i) & 1u)) continue;
+            if (key[i] > T1) prot |= 1u << i;
+            else if (key[i] == T1) { if (rank < take_eq1) prot |= 1u << i; ++rank; }
+        }
+    }
+    // the neighbour's last token
+    __syncthreads();
+    sh.bits[tid + 1] = prot;
+    if (tid == 0) sh.bits[0] = 0;
+    __syncthreads();
+    const uint32_t prot_prev = (prot << 1) | ((sh.bits[tid] >> (SR_ITEMS - 1)) & 1u);   // bit i: token jb+i-1 is conserved
+
+    // j-1 and j may share a set (before the budget rule); "natural" boundary = both free, sim <= eps
+    uint32_t joins = 0, natural = 0;
+#pragma unroll
+    for (int i = 0; i < SR_ITEMS; ++i) {
+        const bool both_free = jb + i >= 1 && jb + i < n && !((prot >> i) & 1u) && !((prot_prev >> i) & 1u);
+        const bool above = sm[i] > eps;
+        joins |= (both_free && above ? 1u : 0u) << i;
+        natural |= (both_free && !above ? 1u : 0u) << i;
+    }
+    int M0, n_nat;
+    (void)block_exclusive_sum_w<WAVES>(__popc(in_n & ~joins), M0, sh.wave_i);
+    (void)block_exclusive_sum_w<WAVES>(__popc(natural), n_nat, sh.wave_i2);
+    int status = 0;
+
+    // ---- budget rule: remove the most similar natural boundaries (ties: higher index first) ------
+    uint32_t removed = 0;
+    if (a.enforce && M0 > cap) {
+        const int r = M0 - cap;
+        const bool all = n_nat <= r;
+        if (n_nat < r) status |= KVM_SLICE_INFEASIBLE;
+        if (n_nat > 0) status |= KVM_SLICE_FALLBACK;
+        if (all) {
+            removed = natural;
+        } else {
+            uint32_t skey[SR_ITEMS];
+#pragma unroll
+            for (int i = 0; i < SR_ITEMS; ++i) skey[i] = sortable_key(sm[i]);
+            uint32_t T2;
+            int gt2;
+            select_kth_largest_reg<BLOCK>(skey, natural, r, T2, gt2, sh);
+            const int take_eq2 = r - gt2;
+            int eq_cnt = 0;
+#pragma unroll
+            for (int i = 0; i < SR_ITEMS; ++i) eq_cnt += (((natural >> i) & 1u) && skey[i] == T2) ? 1 : 0;
+            int total_eq2;
+            int rank = block_exclusive_sum_w<WAVES>(eq_cnt, total_eq2, sh.wave_i);
+#pragma unroll
+            for (int i = 0; i < SR_ITEMS; ++i) {
+                if (!((natural >> i) & 1u)) continue;
+                if (skey[i] > T2) removed |= 1u << i;
+                else if (skey[i] == T2) { if (total_eq2 - 1 - rank < take_eq2) removed |= 1u << i; ++rank; }
+            }
+        }
+    }
+
+    // ---- set ids, set starts, pivots -----------------------------------------------------------
+    // token j starts a set unless it joins its predecessor or its boundary was removed; the position
+    // after the last token closes the last set
+    const uint32_t head = (in_n & ~(joins | removed)) | (~in_n & 0xFFFFu);
+    __syncthreads();
+    sh.bits[tid] = head;
+    if (tid == 0) sh.bits[BLOCK] = 0xFFFFu;
+    __syncthreads();
+    const uint32_t head_next = (head >> 1) | ((sh.bits[tid + 1] & 1u) << (SR_ITEMS - 1));   // bit i: token jb+i+1 starts a set
+    const int heads = __popc(head & in_n);
+    unsigned long long mkey[SR_ITEMS];
+#pragma unroll
+    for (int i = 0; i < SR_ITEMS; ++i) mkey[i] = ((unsigned long long)key[i] << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(jb + i));
+    // thread summary for the segmented max scan: (any head, max of the trailing open segment)
+    int f = 0;
+    unsigned long long k = 0;
+#pragma unroll
+    for (int i = 0; i < SR_ITEMS; ++i) {
+        if (!((in_n >> i) & 1u)) break;
+        if ((head >> i) & 1u) { f = 1; k = mkey[i]; }
+        else k = k > mkey[i] ? k : mkey[i];
+    }
+    int M;
+    const int sets_before = block_exclusive_sum_w<WAVES>(heads, M, sh.wave_i);
+    int fi = f;
+    unsigned long long ki = k;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        int f2 = __shfl_up(fi, off, WAVE);
+        unsigned long long k2 = shfl_up_u64(ki, off);
+        if (lane >= off) {
+            if (!fi) ki = ki > k2 ? ki : k2;
+            fi |= f2;
+        }
+    }
+    if (lane == WAVE - 1) { sh.wave_f[w] = fi; sh.wave_k[w] = ki; }
+    int fe = __shfl_up(fi, 1, WAVE);                         // exclusive within the wave
+    unsigned long long ke = shfl_up_u64(ki, 1);
+    if (lane == 0) { fe = 0; ke = 0; }
+    __syncthreads();
+    unsigned long long kp = 0;                               // everything before this wave
+    for (int i = 0; i < w; ++i) {
+        if (sh.wave_f[i]) kp = sh.wave_k[i];
+        else kp = kp > sh.wave_k[i] ? kp : sh.wave_k[i];
+    }
+    unsigned long long cur = fe ? ke : (kp > ke ? kp : ke);
+    int s = sets_before - 1;
+    int32_t ids[SR_ITEMS];
+#pragma unroll
+    for (int i = 0; i < SR_ITEMS; ++i) {
+        const int j = jb + i;
+        if ((in_n >> i) & 1u) {
+            if ((head >> i) & 1u) {
+                ++s;
+                cur = mkey[i];
+                if (s <= a.cap_rows) set_start[s] = j;
+            } else {
+                cur = cur > mkey[i] ? cur : mkey[i];
+            }
+            if (((head_next >> i) & 1u) && s < a.cap_rows) pivot[s] = (int32_t)(0xFFFFFFFFu - (uint32_t)cur);
+        }
+        ids[i] = s;
+    }
+#pragma unroll
+    for (int v = 0; v < SR_ITEMS / 4; ++v) {
+        if (vec && jb + 4 * v + 3 < n) {
+            int4 o = {ids[4 * v], ids[4 * v + 1], ids[4 * v + 2], ids[4 * v + 3]};
+            *reinterpret_cast<int4 *>(set_id + jb + 4 * v) = o;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (jb + 4 * v + e < n) set_id[jb + 4 * v + e] = ids[4 * v + e];
+        }
+    }
+    for (int t = M + tid; t <= a.cap_rows; t += BLOCK) {
+        set_start[t] = n;
+        if (t < a.cap_rows) pivot[t] = -1;
+    }
+    if (a.pivot_rule != KVM_PIVOT_MAX_SCORE) {
+        // the other pivot rules need only the sets' extents, which are complete now
+        __syncthreads();
+        for (int t = tid; t < min(M, a.cap_rows); t += BLOCK) {
+            const int lo = set_start[t], hi = set_start[t + 1];
+            pivot[t] = a.pivot_rule == KVM_PIVOT_LAST ? hi - 1 : lo + random_member(a.pivot_seed, slice, lo, hi - lo);
+        }
+    }
+    if (M > a.cap_rows) status |= KVM_SLICE_TRUNCATED;
+    if (tid == 0) {
+        a.n_sets[slice] = M;
+        a.slice_status[slice] = status;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // comparison workload: eviction by aggregated attention score
 // ------------------------------------------------------------------------------------------
 
@@ -796,7 +1109,14 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
         }
     }
     ProfScope prof("segment_kernel", st);
-    hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), walk_lds_bytes, st, a);
+    if (!anchor && sh.N > 0 && sh.N <= 1024 * SR_ITEMS) {
+        // 16 tokens per thread in registers: as many threads as the slice needs
+        if (sh.N <= 256 * SR_ITEMS) hipLaunchKernelGGL(segment_reg_kernel<256>, dim3((unsigned)slices), dim3(256), 0, st, a);
+        else if (sh.N <= 512 * SR_ITEMS) hipLaunchKernelGGL(segment_reg_kernel<512>, dim3((unsigned)slices), dim3(512), 0, st, a);
+        else hipLaunchKernelGGL(segment_reg_kernel<1024>, dim3((unsigned)slices), dim3(1024), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(segment_kernel, dim3((unsigned)slices), dim3(SEG_BLOCK), walk_lds_bytes, st, a);
+    }
     return check_launch("segment_kernel");
 }
 
