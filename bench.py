@@ -59,6 +59,9 @@ def main() -> int:
                     help="given = the softmax row statistics are an input, as left behind by a prefill attention kernel "
                          "(kvm_attn_mass_from_lse: only the column-sum pass runs)")
     ap.add_argument("--sigma", type=float, default=None, help="fixed sigma (Section 5.4) instead of the per-set one")
+    ap.add_argument("--keys", choices=["ar1", "identical"], default="ar1",
+                    help="identical = every key of a slice equals its first key: the degenerate case in which all free "
+                         "tokens of a slice form one merging set (worst case of the merge kernel, not the headline)")
     ap.add_argument("--gen-workers", type=int, default=None,
                     help="processes that generate the inputs (1 = in this process, e.g. under a profiler)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -91,6 +94,8 @@ def main() -> int:
             return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
         return torch.from_numpy(x).cuda()
 
+    if args.keys == "identical":
+        K[:] = K[:, :, :1]
     Qd, Kd, Vd = dev(Q), dev(K), dev(V)
     sl = None if lens is None else torch.from_numpy(lens).cuda()
     params = kb.kvm_params_for_budget(args.budget)
@@ -204,7 +209,9 @@ def main() -> int:
     bytes_merge = float(2 * token_slices * d * esz + 2 * M_total * d * esz + 8 * M_total)
     roofline = None
     hbm = {}
-    headline = (args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
+    if args.keys == "identical":
+        variant += "; identical keys (one merging set per slice)"
+    headline = (args.keys == "ar1" and args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
                 and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None)
 
     def traffic(name):

@@ -267,8 +267,9 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
  *               round-to-nearest-even to dtype.
  *   w_opt       out  (B, H_kv, N) float32 or NULL: key weight of every token
  *               (positions not covered by a stored set are not written)
- *   ws          the work plan (first set of every 64-token tile of a slice) is
- *               built there before the merge kernel runs
+ *   ws          the work plan (first set of every 64-token tile of a slice, and the
+ *               slice's sets of more than 512 tokens, which a whole workgroup merges) is
+ *               built there before the merge kernels run
  */
 kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
                      const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,
@@ -278,11 +279,12 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
  * kvm_merge for callers that cannot allocate device memory or may not call an allocator
  * where they run: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, kernels and results as kvm_merge, without the workspace: the
- * work plan (one int32 per 64-token tile of every slice, plus one per slice) is kept in a
+ * work plan (per slice one int32 per 64-token tile, one per possible set of more than 512
+ * tokens, and three more) is kept in a
  * buffer built into the library, KVM_MERGE_STATIC_MAX_PLAN_ENTRIES int32 (8 MiB) on every
  * GPU the library has run this call on, held until the process ends.  The call allocates
  * nothing and frees nothing.
- *   - B * H_kv * (ceil(N / 64) + 1) > KVM_MERGE_STATIC_MAX_PLAN_ENTRIES returns
+ *   - B * H_kv * (ceil(N / 64) + floor(N / 513) + 3) > KVM_MERGE_STATIC_MAX_PLAN_ENTRIES returns
  *     KVM_ERR_WORKSPACE before any launch (use kvm_merge with a workspace then).
  *   - The buffer belongs to the device that is current at the call (the device the tensors
  *     live on); its address is looked up on the first call on that device.

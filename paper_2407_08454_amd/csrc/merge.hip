@@ -20,6 +20,11 @@ namespace kvm {
 constexpr int MERGE_BLOCK = 64;          // one wave per workgroup: waves finish independently
 constexpr int MERGE_TILE = 64;           // tokens per wave (its sets are those that start in the tile)
 constexpr int PLAN_BLOCK = 256;
+// Sets of more than LONG_SET_MIN tokens are left to merge_long_kernel, which puts a whole workgroup
+// on each of them: one wave would stream such a set for hundreds of dependent round trips while
+// the rest of the chip has nothing to do (identical keys make one set of a whole slice).
+constexpr int LONG_SET_MIN = 512;
+constexpr int LONG_SET_BLOCK = 1024;
 // 4-row groups whose loads are issued together: 16 rows of K and of V.  Larger batches read
 // more sets in a single sweep but cost registers; the kernel is bound by memory latency, and
 // four waves per SIMD with 16-row batches beat two waves with 32-row batches.
@@ -28,30 +33,45 @@ template <typename T> struct MergeUnroll { static constexpr int value = 4; };
 struct MergeArgs {
     const int32_t *set_start, *pivot, *n_sets, *seq_lens;
     float *w_opt;
-    const int32_t *plan;    // (slices, tiles_per_slice + 1): first set starting at or after each tile
+    const int32_t *plan;    // (slices, plan_stride): first set starting at or after each of the tiles_per_slice + 1
+                            // tile edges, then the number of long sets of the slice, then their indices
+    int plan_stride;
     int H, N, cap_rows, tiles_per_slice;
     int mode;               // MERGE_ADAPTIVE, MERGE_FIXED (uses inv_two_sigma_sq) or MERGE_AVERAGE
     float inv_two_sigma_sq; // 1 / (2 sigma^2) for the fixed-sigma mode
     int value_scale;
 };
 
-// plan[t] = smallest s with set_start[s] >= t * MERGE_TILE (M if there is none), t = 0..tiles.
+// plan[t] = smallest s with set_start[s] >= t * MERGE_TILE (M if there is none), t = 0..tiles;
+// plan[tiles + 1] = number of sets of more than LONG_SET_MIN tokens, their indices after it (in no
+// particular order: each is merged on its own).
 __global__ __launch_bounds__(PLAN_BLOCK) void merge_plan_kernel(const int32_t *__restrict__ set_start,
                                                                 const int32_t *__restrict__ n_sets,
                                                                 const int32_t *__restrict__ seq_lens, int32_t *__restrict__ plan,
-                                                                int H, int N, int cap_rows, int tiles)
+                                                                int H, int N, int cap_rows, int tiles, int plan_stride)
 {
+    __shared__ int n_long;
     const int slice = blockIdx.x;
     const int n = clamp_len(seq_lens, slice / H, N);
     const int M = min(max(n_sets[slice], 0), cap_rows);
     const int32_t *sst = set_start + (size_t)slice * (cap_rows + 1);
-    int32_t *pl = plan + (size_t)slice * (tiles + 1);
+    int32_t *pl = plan + (size_t)slice * plan_stride;
+    const int max_long = plan_stride - (tiles + 2);
+    if (threadIdx.x == 0) n_long = 0;
+    __syncthreads();
     for (int s = threadIdx.x; s <= M; s += PLAN_BLOCK) {
         const int prev = s > 0 ? min(max(sst[s - 1], 0), n) : -1;
         const int t_lo = prev < 0 ? 0 : prev / MERGE_TILE + 1;
-        const int t_hi = s < M ? min(min(max(sst[s], 0), n) / MERGE_TILE, tiles) : tiles;
+        const int here = min(max(sst[s], 0), n);              // (set_start has an entry for s = M too: the end of the last stored set)
+        const int t_hi = s < M ? min(here / MERGE_TILE, tiles) : tiles;
         for (int t = t_lo; t <= t_hi; ++t) pl[t] = s;
+        if (s > 0 && here - prev > LONG_SET_MIN) {               // set s-1 = [prev, here)
+            const int k = atomicAdd(&n_long, 1);
+            if (k < max_long) pl[tiles + 2 + k] = s - 1;       // (with consistent maps there is always room)
+        }
     }
+    __syncthreads();
+    if (threadIdx.x == 0) pl[tiles + 1] = min(n_long, max_long);
 }
 
 // Squared distance of 8 elements, summed over the 16 lanes of the row.
@@ -88,7 +108,7 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
     const int M = min(max(a.n_sets[slice], 0), a.cap_rows);
     // sets [s_lo, s_hi) start inside this tile (entries are clamped: the plan may hold garbage
     // when the maps are inconsistent)
-    const int32_t *pl = a.plan + (size_t)slice * (a.tiles_per_slice + 1) + tile;
+    const int32_t *pl = a.plan + (size_t)slice * a.plan_stride + tile;
     const int s_lo = min(max(pl[0], 0), M);
     const int s_hi = min(max(pl[1], s_lo), M);
     const int cnt = min(s_hi - s_lo, MERGE_TILE);
@@ -147,7 +167,7 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
         const int lo = __builtin_amdgcn_readlane(my_start, i);
         const int hi = __builtin_amdgcn_readlane(my_next, i);
         const int m = hi - lo;
-        if (m <= 0) { ++i; continue; }                                // inconsistent map: nothing to merge
+        if (m <= 0 || m > LONG_SET_MIN) { ++i; continue; }                // inconsistent map: nothing to merge; long set: merge_long_kernel
         int p = __builtin_amdgcn_readlane(my_piv, i);
         p = min(max(p, lo), hi - 1);
         const Raw kp_raw = E::load(Ks + (size_t)p * HEAD_DIM, c);
@@ -246,6 +266,135 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
     }
 }
 
+// Sets of more than LONG_SET_MIN tokens, one after the other, by all 64 sixteen-lane groups of a
+// 1024-thread workgroup per slice: group g takes the set's rows g, g + 64, ... (four of them in
+// flight), the distance sum and then the weighted sums are added up across the groups through
+// LDS.  Same arithmetic per row as merge_kernel; only the order of the fp32 additions differs.
+template <typename T, bool WITH_W, int MODE>
+__global__ __launch_bounds__(LONG_SET_BLOCK) void merge_long_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                                T *__restrict__ K_out, T *__restrict__ V_out, MergeArgs a)
+{
+    using E = Elem<T>;
+    using Raw = typename E::Raw;
+    constexpr int U = 4;                                     // rows of a group in flight
+    constexpr int GROUPS = LONG_SET_BLOCK / 16, WAVES = LONG_SET_BLOCK / WAVE;
+    __shared__ float red[WAVES][16][17];                     // per wave and chunk lane: 8 key sums, 8 value sums, weight sum
+    __shared__ float red1[WAVES];
+    const int slice = blockIdx.x;
+    const int32_t *pl = a.plan + (size_t)slice * a.plan_stride + a.tiles_per_slice + 1;
+    const int n_long = min(max(pl[0], 0), a.plan_stride - (a.tiles_per_slice + 2));
+    if (n_long == 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = tid & 15, group = tid >> 4;
+    const int n = clamp_len(a.seq_lens, slice / a.H, a.N);
+    const int M = min(max(a.n_sets[slice], 0), a.cap_rows);
+    const int32_t *sst = a.set_start + (size_t)slice * (a.cap_rows + 1);
+    const int32_t *piv = a.pivot + (size_t)slice * a.cap_rows;
+    const T *Ks = K + (size_t)slice * a.N * HEAD_DIM;
+    const T *Vs = V + (size_t)slice * a.N * HEAD_DIM;
+    T *Ko = K_out + (size_t)slice * a.cap_rows * HEAD_DIM;
+    T *Vo = V_out + (size_t)slice * a.cap_rows * HEAD_DIM;
+    float *wo = WITH_W ? a.w_opt + (size_t)slice * a.N : nullptr;
+
+    for (int k = 0; k < n_long; ++k) {
+        const int s = pl[1 + k];
+        if (s < 0 || s >= M) continue;                        // (the same for the whole workgroup)
+        const int lo = min(max(sst[s], 0), n), hi = min(max(sst[s + 1], 0), n);
+        const int m = hi - lo;
+        if (m <= LONG_SET_MIN) continue;
+        const int p = min(max(piv[s], lo), hi - 1);
+        float kp[8];
+        E::to_float(E::load(Ks + (size_t)p * HEAD_DIM, c), kp);
+        float inv_mean = 0.f;
+        if (MODE == MERGE_ADAPTIVE) {
+            float dsum = 0.f;
+            for (int j0 = lo + group; j0 < hi; j0 += GROUPS * U) {
+                Raw kr[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) kr[u] = E::load(Ks + (size_t)min(j0 + GROUPS * u, hi - 1) * HEAD_DIM, c);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    float x[8];
+                    E::to_float(kr[u], x);
+                    const float dist = __builtin_amdgcn_sqrtf(sq_dist16(kp, x));
+                    dsum += (j0 + GROUPS * u < hi) ? dist : 0.f;
+                }
+            }
+            dsum = rows4_sum(dsum);                           // the wave's four groups
+            __syncthreads();                                  // red1 may still be read from the set before
+            if (lane == 0) red1[wave] = dsum;
+            __syncthreads();
+            float total = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < WAVES; ++w2) total += red1[w2];
+            inv_mean = total > 0.f ? (float)m / total : 0.f;
+        }
+        float ak[8], av[8], gsum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ak[e] = 0.f; av[e] = 0.f; }
+        for (int j0 = lo + group; j0 < hi; j0 += GROUPS * U) {
+            Raw kr[U], vr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t row = (size_t)min(j0 + GROUPS * u, hi - 1) * HEAD_DIM;
+                kr[u] = E::load(Ks + row, c);
+                vr[u] = E::load(Vs + row, c);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = j0 + GROUPS * u;
+                float x[8], v[8];
+                E::to_float(kr[u], x);
+                float g;
+                if (MODE == MERGE_AVERAGE) {
+                    g = 1.f;
+                } else if (MODE == MERGE_FIXED) {
+                    g = __expf(-sq_dist16(kp, x) * a.inv_two_sigma_sq);
+                } else {
+                    const float r = __builtin_amdgcn_sqrtf(sq_dist16(kp, x)) * inv_mean;
+                    g = __expf(-r * r);
+                }
+                g = row < hi ? g : 0.f;
+                gsum += g;
+                E::to_float(vr[u], v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { ak[e] = fmaf(g, x[e], ak[e]); av[e] = fmaf(g, v[e], av[e]); }
+                if (WITH_W && c == 0 && row < hi) wo[row] = g;
+            }
+        }
+        gsum = rows4_sum(gsum);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ak[e] = rows4_sum(ak[e]); av[e] = rows4_sum(av[e]); }
+        __syncthreads();                                      // red may still be read from the set before
+        if (lane < 16) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { red[wave][c][e] = ak[e]; red[wave][c][8 + e] = av[e]; }
+            red[wave][c][16] = gsum;
+        }
+        __syncthreads();
+        float gtot = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < WAVES; ++w2) gtot += red[w2][0][16];
+        const float inv_g = 1.f / gtot;
+        if (tid < 32) {                                       // lanes 0..15: the key row, 16..31: the value row
+            const bool is_v = tid >= 16;
+            const float scale = is_v && a.value_scale ? inv_g * (float)m : inv_g;
+            float out[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float t = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < WAVES; ++w2) t += red[w2][c][(is_v ? 8 : 0) + e];
+                out[e] = t * scale;
+            }
+            E::store((is_v ? Vo : Ko) + (size_t)s * HEAD_DIM, c, E::from_float(out));
+        }
+        if (WITH_W && c == 0) {                               // each writer normalises its own g_j
+            for (int row = lo + group; row < hi; row += GROUPS) wo[row] *= inv_g;
+        }
+    }
+}
+
 template <typename T>
 static void launch_merge_t(const kvm_shape &sh, const void *K, const void *V, void *K_out, void *V_out,
                            const MergeArgs &a, hipStream_t st)
@@ -266,10 +415,35 @@ static void launch_merge_t(const kvm_shape &sh, const void *K, const void *V, vo
     }
 }
 
+template <typename T>
+static void launch_merge_long_t(const kvm_shape &sh, const void *K, const void *V, void *K_out, void *V_out,
+                                const MergeArgs &a, hipStream_t st)
+{
+    ProfScope prof("merge_long_kernel", st);
+    const dim3 grid((unsigned)((long long)sh.B * sh.H_kv)), block(LONG_SET_BLOCK);
+    const T *k = (const T *)K, *v = (const T *)V;
+    T *ko = (T *)K_out, *vo = (T *)V_out;
+    if (a.w_opt) {
+        if (a.mode == MERGE_AVERAGE) hipLaunchKernelGGL((merge_long_kernel<T, true, MERGE_AVERAGE>), grid, block, 0, st, k, v, ko, vo, a);
+        else if (a.mode == MERGE_FIXED) hipLaunchKernelGGL((merge_long_kernel<T, true, MERGE_FIXED>), grid, block, 0, st, k, v, ko, vo, a);
+        else hipLaunchKernelGGL((merge_long_kernel<T, true, MERGE_ADAPTIVE>), grid, block, 0, st, k, v, ko, vo, a);
+    } else {
+        if (a.mode == MERGE_AVERAGE) hipLaunchKernelGGL((merge_long_kernel<T, false, MERGE_AVERAGE>), grid, block, 0, st, k, v, ko, vo, a);
+        else if (a.mode == MERGE_FIXED) hipLaunchKernelGGL((merge_long_kernel<T, false, MERGE_FIXED>), grid, block, 0, st, k, v, ko, vo, a);
+        else hipLaunchKernelGGL((merge_long_kernel<T, false, MERGE_ADAPTIVE>), grid, block, 0, st, k, v, ko, vo, a);
+    }
+}
+
+// int32 entries of a slice's plan: tiles + 1 tile edges, the number of long sets, their indices
+static int merge_plan_stride(int N)
+{
+    const int tiles = (N + MERGE_TILE - 1) / MERGE_TILE;
+    return tiles + 2 + N / (LONG_SET_MIN + 1) + 1;
+}
+
 size_t merge_workspace_bytes(const kvm_shape &sh)
 {
-    const size_t tiles = ((size_t)sh.N + MERGE_TILE - 1) / MERGE_TILE;
-    return (size_t)sh.B * sh.H_kv * (tiles + 1) * sizeof(int32_t);
+    return (size_t)sh.B * sh.H_kv * merge_plan_stride(sh.N) * sizeof(int32_t);
 }
 
 kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
@@ -288,13 +462,14 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     a.N = sh.N;
     a.cap_rows = cap_rows;
     a.tiles_per_slice = (sh.N + MERGE_TILE - 1) / MERGE_TILE;
+    a.plan_stride = merge_plan_stride(sh.N);
     a.mode = pr.weights == KVM_WEIGHTS_AVERAGE ? MERGE_AVERAGE : (pr.sigma_mode == KVM_SIGMA_FIXED ? MERGE_FIXED : MERGE_ADAPTIVE);
     a.inv_two_sigma_sq = a.mode == MERGE_FIXED ? 1.f / (2.f * pr.sigma * pr.sigma) : 0.f;
     a.value_scale = pr.value_scale_by_set_size;
     {
         ProfScope prof("merge_plan_kernel", st);
         hipLaunchKernelGGL(merge_plan_kernel, dim3((unsigned)(sh.B * sh.H_kv)), dim3(PLAN_BLOCK), 0, st, set_start, n_sets,
-                           sh.seq_lens, plan, sh.H_kv, sh.N, cap_rows, a.tiles_per_slice);
+                           sh.seq_lens, plan, sh.H_kv, sh.N, cap_rows, a.tiles_per_slice, a.plan_stride);
         kvm_status rc = check_launch("merge_plan_kernel");
         if (rc != KVM_OK) return rc;
     }
@@ -303,7 +478,14 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     case KVM_F16: launch_merge_t<half_t>(sh, K, V, K_out, V_out, a, st); break;
     default: launch_merge_t<bf16_t>(sh, K, V, K_out, V_out, a, st); break;
     }
-    return check_launch("merge_kernel");
+    kvm_status rc = check_launch("merge_kernel");
+    if (rc != KVM_OK || sh.N <= LONG_SET_MIN) return rc;          // (no slice can hold a long set)
+    switch (sh.dtype) {
+    case KVM_F32: launch_merge_long_t<float>(sh, K, V, K_out, V_out, a, st); break;
+    case KVM_F16: launch_merge_long_t<half_t>(sh, K, V, K_out, V_out, a, st); break;
+    default: launch_merge_long_t<bf16_t>(sh, K, V, K_out, V_out, a, st); break;
+    }
+    return check_launch("merge_long_kernel");
 }
 
 // ------------------------------------------------------------------------------------------
@@ -348,7 +530,7 @@ kvm_status launch_merge_static(const kvm_shape &sh, const kvm_params &pr, int ca
 {
     const size_t need = merge_workspace_bytes(sh) / sizeof(int32_t);
     if (need > STATIC_PLAN_INTS) {
-        set_error("kvm_merge_static: the work plan needs %zu entries (B*H_kv*(ceil(N/64)+1)), the built-in buffer holds %zu; "
+        set_error("kvm_merge_static: the work plan needs %zu entries (B*H_kv*(ceil(N/64)+floor(N/513)+3)), the built-in buffer holds %zu; "
                   "use kvm_merge with a workspace", need, STATIC_PLAN_INTS);
         return KVM_ERR_WORKSPACE;
     }

@@ -659,6 +659,42 @@ def test_merge_degenerate_sets():
     _check_merge(K, V, "f32", o, *res, "truncated")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("mode", ["gaussian", "fixed_sigma", "average", "no_value_scale"])
+def test_merge_sets_around_the_length_a_workgroup_takes_over(dtype, mode):
+    """Hand-made partitions with sets of 512 tokens (still one wave's), 513 and 2000 tokens (merged by a
+    whole workgroup), short sets and singletons between them, ragged lengths; every weighting."""
+    n = 3600
+    _say(f"merge: long sets, {dtype}, {mode}")
+    rng = np.random.default_rng(77)
+    lens = [n, 1500, 513]
+    Q, K, V = _slices(34, 3, 2, lens, n, 128, 1, dtype, rho=0.97)
+    sizes = [[512, 513, 5, 1, 2000, 17, 1, 1, 64, 486], [700, 1, 1, 513, 285], [513]]
+    params = kb.make_params(1.0, 0.0, 0.0, enforce_budget=False)
+    if mode == "fixed_sigma":
+        params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, 4.0
+    elif mode == "average":
+        params.weights = kb.KVM_WEIGHTS_AVERAGE
+    elif mode == "no_value_scale":
+        params.value_scale_by_set_size = 0
+    cap = n
+    st = np.zeros((3, 2, cap + 1), np.int32)
+    pv = np.full((3, 2, cap), -1, np.int32)
+    ns = np.zeros((3, 2), np.int32)
+    for b in range(3):
+        assert sum(sizes[b]) == lens[b]
+        for h in range(2):
+            starts = np.concatenate([[0], np.cumsum(sizes[b])])
+            M = len(sizes[b])
+            st[b, h, :M + 1] = starts
+            st[b, h, M + 1:] = lens[b]
+            pv[b, h, :M] = starts[:-1] + rng.integers(0, sizes[b])
+            ns[b, h] = M
+    o = dict(set_start=st, pivot=pv, n_sets=ns, cap_rows=cap)
+    res = _merge_both(K, V, dtype, params, o, lens)
+    _check_merge(K, V, dtype, o, *res, f"long sets {dtype} {mode}")
+
+
 def test_merge_tolerates_inconsistent_maps():
     n = 256
     _say("merge: out-of-range map entries are clamped, nothing faults")
