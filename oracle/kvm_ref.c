@@ -627,6 +627,16 @@ int kvm_ref_num_threads(void)
 #endif
 }
 
+/* Sets that number (the benchmark also times the oracle on a single thread).  No arithmetic here. */
+void kvm_ref_set_num_threads(int k)
+{
+#ifdef _OPENMP
+    if (k >= 1) omp_set_num_threads(k);
+#else
+    (void)k;
+#endif
+}
+
 /* The pivot generator, exported for the tests (published test vectors). */
 uint64_t kvm_ref_splitmix64_at(uint64_t z) { return splitmix64_at(z); }
 int kvm_ref_random_offset(uint64_t seed, int bh, int lo, int m) { return random_offset(seed, bh, lo, m); }

@@ -89,6 +89,11 @@ def num_threads() -> int:
     return int(_load().kvm_ref_num_threads())
 
 
+def set_num_threads(k: int) -> None:
+    """Threads the oracle's loops over slices use from now on (the OpenMP runtime's own switch)."""
+    _load().kvm_ref_set_num_threads(int(k))
+
+
 def attn_mass(Q, K, dtype: str, G: int = 1, seq_lens=None):
     """Q (B, H*G, N, d), K (B, H, N, d) -> mass (B, H, N) fp64."""
     lib = _load()
