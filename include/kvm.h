@@ -276,6 +276,31 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
                      void *K_out, void *V_out, float *w_opt, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Decode-time companion of kvm_merge (the paper runs its method on the prefilled cache and says
+ * nothing of decoding; this call only avoids redoing work whose result is already known).  After
+ * kvm_attn_mass_append, kvm_sim_append and kvm_identify_sets on the grown sequence, most sets of
+ * the new maps are sets of the previous maps: same first token, same end, same pivot, hence the
+ * same merged state (Def. 4.2 Eq. (4)-(6) depend on nothing else).  Their rows are moved to their
+ * new index inside K_out / V_out; only the other sets are merged again.  The result equals what
+ * kvm_merge gives on the new maps, bit for bit.
+ *   K, V          in      (B, H_kv, N, d): rows of tokens that existed at the previous call unchanged
+ *   prev_set_id, prev_set_start, prev_pivot, prev_n_sets
+ *                 in      the maps K_out / V_out were merged with (as kvm_identify_sets wrote them;
+ *                         buffers different from the new maps)
+ *   set_start, pivot, n_sets  in   the new maps
+ *   K_out, V_out  in/out  (B, H_kv, capacity, d): the compacted cache of the previous maps on entry,
+ *                         of the new maps on return
+ *   n_changed_opt out     (B, H_kv) int32 or NULL: sets that were merged again
+ *   ws            kvm_workspace_bytes(shape, params) is enough
+ * params (weights, sigma, value scaling) must be those of the previous merge.  Not for w_opt.
+ */
+kvm_status kvm_merge_refresh(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                             const int32_t *prev_set_id, const int32_t *prev_set_start,
+                             const int32_t *prev_pivot, const int32_t *prev_n_sets, const int32_t *set_start,
+                             const int32_t *pivot, const int32_t *n_sets, void *K_out, void *V_out,
+                             int32_t *n_changed_opt, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * kvm_merge for callers that cannot allocate device memory or may not call an allocator
  * where they run: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, kernels and results as kvm_merge, without the workspace: the

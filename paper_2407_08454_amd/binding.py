@@ -25,7 +25,7 @@ KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
            "kvm_attn_mass_from_lse", "kvm_attn_mass_append", "kvm_sim_append",
-           "kvm_identify_sets", "kvm_merge", "kvm_merge_static", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
+           "kvm_identify_sets", "kvm_merge", "kvm_merge_refresh", "kvm_merge_static", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
 _TORCH_DTYPE = {torch.float32: KVM_F32, torch.float16: KVM_F16, torch.bfloat16: KVM_BF16}
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_identify_sets.restype = ctypes.c_int
     lib.kvm_merge.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9 + [S, P]
     lib.kvm_merge.restype = ctypes.c_int
+    lib.kvm_merge_refresh.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 13 + [S, P]
+    lib.kvm_merge_refresh.restype = ctypes.c_int
     lib.kvm_merge_static.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 9
     lib.kvm_merge_static.restype = ctypes.c_int
     lib.kvm_evict.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 8 + [S, P]
@@ -268,6 +270,23 @@ def kvm_merge(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets
         ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(set_start), _ptr(pivot), _ptr(n_sets),
         _ptr(K_out), _ptr(V_out), _ptr(w_opt), None if ws is None else _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_merge_refresh(shape: KvmShape, params: KvmParams, K, V, prev_set_id, prev_set_start, prev_pivot, prev_n_sets,
+                      set_start, pivot, n_sets, K_out, V_out, n_changed, ws):
+    """K_out / V_out, merged with the previous maps, become the compacted cache of the new maps: rows of sets
+    that did not change move to their new index, the others are merged again."""
+    _check_merge_operands(shape, params, K, V, set_start, pivot, n_sets, K_out, V_out, None, ws)
+    _same_device(prev_set_id, prev_set_start, prev_pivot, prev_n_sets, n_changed)
+    B, H, N = shape.B, shape.H_kv, shape.N
+    for t, other, shp in ((prev_set_id, None, (B, H, N)), (prev_set_start, set_start, None), (prev_pivot, pivot, None),
+                          (prev_n_sets, n_sets, None)) + (((n_changed, None, (B, H)),) if n_changed is not None else ()):
+        if t.dtype != torch.int32 or tuple(t.shape) != (shp if shp is not None else tuple(other.shape)):
+            raise ValueError("previous maps must be int32 tensors shaped like the new ones")
+    _check("kvm_merge_refresh", load_library().kvm_merge_refresh(
+        ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(prev_set_id), _ptr(prev_set_start),
+        _ptr(prev_pivot), _ptr(prev_n_sets), _ptr(set_start), _ptr(pivot), _ptr(n_sets), _ptr(K_out), _ptr(V_out),
+        _ptr(n_changed), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def kvm_merge_static(shape: KvmShape, params: KvmParams, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt):

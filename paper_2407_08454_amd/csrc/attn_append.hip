@@ -9,9 +9,10 @@
 // spans the whole row:
 //   append_scores_kernel      thread j of a workgroup owns key j of a 256-key tile; a row is
 //                             spread over 16 lanes as in the other streaming kernels.  Scores
-//                             (base-2 logarithm units) go to the workspace, with the tile's
-//                             maximum and sum of exponentials beside them.
-//   append_accumulate_kernel  merges the tiles' statistics of a query head into its
+//                             (base-2 logarithm units) go to the workspace, with the maximum
+//                             and the sum of exponentials of every wave's 64 keys beside them
+//                             (no exchange between waves, so no barrier).
+//   append_accumulate_kernel  merges the waves' statistics of a query head into its
 //                             log-sum-exp and adds exp2(score - lse) of all G heads to mass.
 #include "kvm_common.h"
 
@@ -20,6 +21,8 @@ namespace kvm {
 constexpr int APP_BLOCK = 256;
 constexpr int APP_ROWS_PER_GROUP = 16;                      // one row per lane of the group in the end
 constexpr int APP_WAVES = APP_BLOCK / WAVE;
+constexpr int ACC_PER_THREAD = 8;                           // keys per thread of the second kernel
+constexpr int ACC_CHUNK = APP_BLOCK * ACC_PER_THREAD;
 
 int attn_lse_stride(int N);
 
@@ -34,25 +37,6 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Maximum and sum of exp2(x - maximum) over the workgroup's values (x = -inf contributes nothing;
-// at least one value of the workgroup is finite).  Every thread gets both.
-__device__ __forceinline__ void block_max_sumexp(float x, float &m, float &l, float *slots) {
-    const int w = threadIdx.x >> 6;
-    const float wm = wave_max(x);
-    __syncthreads();                                         // slots may still be read from a previous use
-    if ((threadIdx.x & 63) == 0) slots[w] = wm;
-    __syncthreads();
-    m = slots[0];
-#pragma unroll
-    for (int i = 1; i < APP_WAVES; ++i) m = fmaxf(m, slots[i]);
-    const float ws = wave_sum(__builtin_amdgcn_exp2f(x - m));
-    if ((threadIdx.x & 63) == 0) slots[APP_WAVES + w] = ws;
-    __syncthreads();
-    l = 0.f;
-#pragma unroll
-    for (int i = 0; i < APP_WAVES; ++i) l += slots[APP_WAVES + i];
-}
-
 template <typename T>
 __global__ __launch_bounds__(APP_BLOCK) void append_scores_kernel(const T *__restrict__ q_new, const T *__restrict__ K,
                                                                    float *__restrict__ scores, float *__restrict__ stats,
@@ -60,15 +44,14 @@ __global__ __launch_bounds__(APP_BLOCK) void append_scores_kernel(const T *__res
                                                                    int N, int n_pad, int tiles_per_slice, float c)
 {
     typedef typename Elem<T>::Raw Raw;
-    __shared__ float slots[2 * APP_WAVES];
     const int slice = blockIdx.x / tiles_per_slice;          // (b, h)
     const int tile = blockIdx.x - slice * tiles_per_slice;
     const int b = slice / H;
     const int n = clamp_len(seq_lens, b, N);
-    const int j_block = tile * APP_BLOCK;
-    if (j_block >= n) return;                                // the other kernel looks at tiles below n only
+    const int j_wave = tile * APP_BLOCK + (threadIdx.x & ~63);   // a wave's 64 keys share one pair of statistics
+    if (j_wave >= n) return;                                 // the other kernel looks at keys below n only
     const int lane16 = threadIdx.x & 15, group = threadIdx.x >> 4;
-    const int j0 = j_block + group * APP_ROWS_PER_GROUP;
+    const int j0 = tile * APP_BLOCK + group * APP_ROWS_PER_GROUP;
     const T *Ks = K + (size_t)slice * N * HEAD_DIM;
 
     // all rows of the group at once; rows past the end repeat the last valid one and are masked below
@@ -76,7 +59,8 @@ __global__ __launch_bounds__(APP_BLOCK) void append_scores_kernel(const T *__res
 #pragma unroll
     for (int i = 0; i < APP_ROWS_PER_GROUP; ++i) raw[i] = Elem<T>::load(Ks + (size_t)min(j0 + i, n - 1) * HEAD_DIM, lane16);
 
-    const int j = j_block + threadIdx.x;                     // the key whose score this thread keeps
+    const int j = tile * APP_BLOCK + threadIdx.x;            // the key whose score this thread keeps
+    const int stats_per_row = n_pad / WAVE;
     for (int g = 0; g < G; ++g) {
         const size_t qslice = (size_t)slice * G + g;
         const Raw q = Elem<T>::load(q_new + qslice * HEAD_DIM, lane16);
@@ -88,10 +72,10 @@ __global__ __launch_bounds__(APP_BLOCK) void append_scores_kernel(const T *__res
         }
         const float x = j < n ? mine * c : -INFINITY;
         if (j < n) scores[qslice * n_pad + j] = x;
-        float m, l;
-        block_max_sumexp(x, m, l, slots);
-        if (threadIdx.x == 0) {
-            float *st = stats + (qslice * tiles_per_slice + tile) * 2;
+        const float m = wave_max(x);                         // finite: key j_wave is below n
+        const float l = wave_sum(__builtin_amdgcn_exp2f(x - m));
+        if ((threadIdx.x & 63) == 0) {
+            float *st = stats + (qslice * stats_per_row + j_wave / WAVE) * 2;
             st[0] = m;
             st[1] = l;
         }
@@ -101,21 +85,23 @@ __global__ __launch_bounds__(APP_BLOCK) void append_scores_kernel(const T *__res
 __global__ __launch_bounds__(APP_BLOCK) void append_accumulate_kernel(const float *__restrict__ scores,
                                                                        const float *__restrict__ stats, float *__restrict__ mass,
                                                                        const int32_t *__restrict__ seq_lens, int H, int G, int N,
-                                                                       int n_pad, int tiles_per_slice)
+                                                                       int n_pad, int chunks_per_slice)
 {
     __shared__ float slots[2 * APP_WAVES];
-    const int slice = blockIdx.x / tiles_per_slice;
-    const int tile = blockIdx.x - slice * tiles_per_slice;
+    const int slice = blockIdx.x / chunks_per_slice;
+    const int chunk = blockIdx.x - slice * chunks_per_slice;
     const int n = clamp_len(seq_lens, slice / H, N);
-    const int j_block = tile * APP_BLOCK;
+    const int j_block = chunk * ACC_CHUNK;
     if (j_block >= n) return;
-    const int valid_tiles = (n + APP_BLOCK - 1) / APP_BLOCK;
-    const int j = j_block + threadIdx.x;
-    float add = 0.f;
+    const int valid_tiles = (n + WAVE - 1) / WAVE;           // statistics come per 64 keys
+    const int stats_per_row = n_pad / WAVE;
+    float add[ACC_PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < ACC_PER_THREAD; ++u) add[u] = 0.f;
     for (int g = 0; g < G; ++g) {
         const size_t qslice = (size_t)slice * G + g;
-        const float *st = stats + qslice * tiles_per_slice * 2;
-        // log-sum-exp of the row from the tiles' statistics: threads take tiles in turn, then the
+        const float *st = stats + qslice * stats_per_row * 2;
+        // log-sum-exp of the row from the waves' statistics: threads take them in turn, then the
         // workgroup reduces (two steps of the same rule: maximum first, sums scaled to it)
         float tm = -INFINITY;
         for (int t = threadIdx.x; t < valid_tiles; t += APP_BLOCK) tm = fmaxf(tm, st[2 * t]);
@@ -135,11 +121,19 @@ __global__ __launch_bounds__(APP_BLOCK) void append_accumulate_kernel(const floa
 #pragma unroll
         for (int i = 0; i < APP_WAVES; ++i) l += slots[APP_WAVES + i];
         const float lse = m + __log2f(l);
-        if (j < n) add += __builtin_amdgcn_exp2f(scores[qslice * n_pad + j] - lse);
+#pragma unroll
+        for (int u = 0; u < ACC_PER_THREAD; ++u) {
+            const int j = j_block + u * APP_BLOCK + threadIdx.x;
+            if (j < n) add[u] += __builtin_amdgcn_exp2f(scores[qslice * n_pad + j] - lse);
+        }
     }
-    if (j < n) {
-        float *a = mass + (size_t)slice * N + j;
-        *a = j == n - 1 ? add : *a + add;                    // the newest token's entry starts here
+#pragma unroll
+    for (int u = 0; u < ACC_PER_THREAD; ++u) {
+        const int j = j_block + u * APP_BLOCK + threadIdx.x;
+        if (j < n) {
+            float *a = mass + (size_t)slice * N + j;
+            *a = j == n - 1 ? add[u] : *a + add[u];          // the newest token's entry starts here
+        }
     }
 }
 
@@ -160,12 +154,13 @@ static kvm_status launch_t(const kvm_shape &sh, const void *q_new, const void *K
     kvm_status rc = check_launch("append_scores_kernel");
     if (rc != KVM_OK) return rc;
     ProfScope prof("append_accumulate_kernel", st);
-    hipLaunchKernelGGL(append_accumulate_kernel, dim3((unsigned)blocks), dim3(APP_BLOCK), 0, st, (const float *)scores,
-                       (const float *)stats, mass, sh.seq_lens, sh.H_kv, sh.G, sh.N, n_pad, tiles);
+    const int chunks = (sh.N + ACC_CHUNK - 1) / ACC_CHUNK;
+    hipLaunchKernelGGL(append_accumulate_kernel, dim3((unsigned)((long long)sh.B * sh.H_kv * chunks)), dim3(APP_BLOCK), 0, st,
+                       (const float *)scores, (const float *)stats, mass, sh.seq_lens, sh.H_kv, sh.G, sh.N, n_pad, chunks);
     return check_launch("append_accumulate_kernel");
 }
 
-// ws: scores (B H_kv G, stride attn_lse_stride(N)) followed by two floats per (query slice, 256-key tile).
+// ws: scores (B H_kv G, stride attn_lse_stride(N)) followed by two floats per (query slice, 64 keys).
 kvm_status launch_attn_append(const kvm_shape &sh, const void *q_new, const void *K, float *mass, float *ws, hipStream_t st)
 {
     if ((long long)sh.B * sh.H_kv == 0 || sh.N == 0) return KVM_OK;

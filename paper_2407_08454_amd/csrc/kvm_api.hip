@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/kvm.h: argument validation, workspace
 // carving, error strings and kernel dispatch.  No allocation, no synchronisation.
 #include <math.h>
+#include <algorithm>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -125,9 +126,11 @@ static int capacity(const kvm_shape *sh, const kvm_params *pr)
 static size_t ws_attn(const kvm_shape *sh)
 {
     // row statistics, then one flag per (query slice, row tile); the decode-time update keeps its
-    // scores in the first part and two floats per (query slice, tile) in the second
+    // scores in the first part and two floats per (query slice, 64 keys) in the second, which is
+    // the larger need
     const size_t q_slices = (size_t)sh->B * sh->H_kv * sh->G;
-    return align_up(q_slices * attn_lse_stride(sh->N) * sizeof(float) + q_slices * attn_row_tiles(sh->N) * 2 * sizeof(float), 256);
+    const size_t second = std::max((size_t)attn_row_tiles(sh->N), (size_t)attn_lse_stride(sh->N) / 64 * 2);
+    return align_up(q_slices * attn_lse_stride(sh->N) * sizeof(float) + q_slices * second * sizeof(float), 256);
 }
 static size_t ws_identify(const kvm_shape *sh)
 {
@@ -175,8 +178,10 @@ int32_t kvm_out_capacity(const kvm_shape *shape, const kvm_params *params)
 size_t kvm_workspace_bytes(const kvm_shape *shape, const kvm_params *params)
 {
     if (check_shape(shape, "kvm_workspace_bytes") != KVM_OK) return 0;
-    (void)params;
-    const size_t a = ws_attn(shape), b = ws_identify(shape), c = merge_workspace_bytes(*shape);
+    // (the refresh of a compacted cache needs two ints per output row on top of the merge plan; without
+    // params the capacity is taken as N)
+    const int cap = params && check_params(params, "kvm_workspace_bytes") == KVM_OK ? capacity(shape, params) : shape->N;
+    const size_t a = ws_attn(shape), b = ws_identify(shape), c = merge_refresh_workspace_bytes(*shape, cap);
     return (a > b ? (a > c ? a : c) : (b > c ? b : c)) + 256;
 }
 
@@ -307,6 +312,35 @@ kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const voi
     }
     return launch_merge(*shape, *params, cap, K, V, set_start, pivot, n_sets, K_out, V_out, w_opt, (int32_t *)ws,
                         (hipStream_t)stream);
+}
+
+kvm_status kvm_merge_refresh(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                             const int32_t *prev_set_id, const int32_t *prev_set_start, const int32_t *prev_pivot,
+                             const int32_t *prev_n_sets, const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets,
+                             void *K_out, void *V_out, int32_t *n_changed_opt, void *ws, size_t ws_bytes, void *stream)
+{
+    kvm_status rc = check_shape(shape, "kvm_merge_refresh");
+    if (rc != KVM_OK) return rc;
+    rc = check_params(params, "kvm_merge_refresh");
+    if (rc != KVM_OK) return rc;
+    const int cap = capacity(shape, params);
+    if ((long long)shape->B * shape->N == 0 || cap == 0) return KVM_OK;
+    if (!K || !V || !prev_set_id || !prev_set_start || !prev_pivot || !prev_n_sets || !set_start || !pivot || !n_sets || !K_out ||
+        !V_out) {
+        set_error("kvm_merge_refresh: a required pointer is NULL");
+        return KVM_ERR_INVALID_ARG;
+    }
+    if (prev_set_start == set_start || prev_pivot == pivot || prev_n_sets == n_sets) {
+        set_error("kvm_merge_refresh: the previous and the new maps must be different buffers");
+        return KVM_ERR_INVALID_ARG;
+    }
+    const size_t need = merge_refresh_workspace_bytes(*shape, cap);
+    if (!ws || ws_bytes < need) {
+        set_error("kvm_merge_refresh: workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
+        return KVM_ERR_WORKSPACE;
+    }
+    return launch_merge_refresh(*shape, *params, cap, K, V, prev_set_id, prev_set_start, prev_pivot, prev_n_sets, set_start, pivot,
+                                n_sets, K_out, V_out, n_changed_opt, (int32_t *)ws, (hipStream_t)stream);
 }
 
 kvm_status kvm_merge_static(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,

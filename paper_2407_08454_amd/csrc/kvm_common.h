@@ -200,6 +200,11 @@ kvm_status launch_evict(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
                         const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, uint8_t *flags,
                         hipStream_t st);
 size_t merge_workspace_bytes(const kvm_shape &sh);
+size_t merge_refresh_workspace_bytes(const kvm_shape &sh, int cap_rows);
+kvm_status launch_merge_refresh(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
+                                const int32_t *prev_set_id, const int32_t *prev_set_start, const int32_t *prev_pivot,
+                                const int32_t *prev_n_sets, const int32_t *set_start, const int32_t *pivot,
+                                const int32_t *n_sets, void *K_out, void *V_out, int32_t *n_changed, int32_t *ws, hipStream_t st);
 int attn_lse_stride(int N);
 int attn_row_tiles(int N);
 

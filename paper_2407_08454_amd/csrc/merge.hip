@@ -30,6 +30,18 @@ constexpr int LONG_SET_BLOCK = 1024;
 // four waves per SIMD with 16-row batches beat two waves with 32-row batches.
 template <typename T> struct MergeUnroll { static constexpr int value = 4; };
 
+// int32 entries of a slice's plan: tiles + 1 tile edges, the number of long sets, their indices
+static int merge_plan_stride(int N)
+{
+    const int tiles = (N + MERGE_TILE - 1) / MERGE_TILE;
+    return tiles + 2 + N / (LONG_SET_MIN + 1) + 1;
+}
+
+size_t merge_workspace_bytes(const kvm_shape &sh)
+{
+    return (size_t)sh.B * sh.H_kv * merge_plan_stride(sh.N) * sizeof(int32_t);
+}
+
 struct MergeArgs {
     const int32_t *set_start, *pivot, *n_sets, *seq_lens;
     float *w_opt;
@@ -90,14 +102,120 @@ __device__ __forceinline__ float sq_dist16(const float *kp, const float *x) {
 // branches and the compiler can interleave the independent rows.
 enum { MERGE_ADAPTIVE = 0, MERGE_FIXED = 1, MERGE_AVERAGE = 2 };
 
+// One set [lo, hi) of 1 .. LONG_SET_MIN tokens with pivot p (lo <= p < hi), merged by one wave into
+// the rows k_row, v_row.  Shared by merge_kernel and the refresh of single sets, so that a set gives
+// the same bits wherever it is merged.
+template <typename T, bool WITH_W, int MODE>
+__device__ __forceinline__ void merge_one_set(const T *Ks, const T *Vs, T *k_row, T *v_row, float *wo, int lo, int hi, int p,
+                                              const MergeArgs &a, int lane)
+{
+    using E = Elem<T>;
+    using Raw = typename E::Raw;
+    constexpr int U = MergeUnroll<T>::value;   // row groups (of 4 rows) in flight
+    const int slot = lane >> 4;          // which of the four rows of an instruction
+    const int c = lane & 15;             // which 8-element chunk of the row
+    const int m = hi - lo;
+    const Raw kp_raw = E::load(Ks + (size_t)p * HEAD_DIM, c);
+    float kp[8];
+    float ak[8], av[8], gsum = 0.f, inv_mean = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ak[e] = 0.f; av[e] = 0.f; }
+    // Rows past the end of the set are clamped to its last row and given weight zero, so
+    // that every lane runs the same straight-line code.
+    auto load_rows = [&](const T *base, int j0, Raw *r) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = E::load(base + (size_t)min(j0 + 4 * u + slot, hi - 1) * HEAD_DIM, c);
+    };
+    auto distances = [&](int j0, const Raw *kr) {
+        float acc = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float x[8];
+            E::to_float(kr[u], x);
+            const float dist = __builtin_amdgcn_sqrtf(sq_dist16(kp, x));
+            acc += (j0 + 4 * u + slot < hi) ? dist : 0.f;
+        }
+        return acc;
+    };
+    // g_j = exp(-D_j^2 / (2 sigma^2)); with sigma = dsum / (sqrt(2) m) that is exp(-(D_j m / dsum)^2)
+    auto accumulate = [&](int j0, const Raw *kr, const Raw *vr) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = j0 + 4 * u + slot;
+            float x[8], v[8];
+            E::to_float(kr[u], x);
+            float g;
+            if (MODE == MERGE_AVERAGE) {
+                g = 1.f;
+            } else if (MODE == MERGE_FIXED) {
+                g = __expf(-sq_dist16(kp, x) * a.inv_two_sigma_sq);
+            } else {
+                const float r = __builtin_amdgcn_sqrtf(sq_dist16(kp, x)) * inv_mean;
+                g = __expf(-r * r);
+            }
+            g = row < hi ? g : 0.f;
+            gsum += g;
+            E::to_float(vr[u], v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { ak[e] = fmaf(g, x[e], ak[e]); av[e] = fmaf(g, v[e], av[e]); }
+            if (WITH_W && c == 0 && row < hi) wo[row] = g;
+        }
+    };
+
+    if (m <= 4 * U) {
+        // the whole set is read once: all loads issued together, both sweeps from registers
+        Raw k0[U], v0[U];
+        load_rows(Ks, lo, k0);
+        load_rows(Vs, lo, v0);
+        E::to_float(kp_raw, kp);
+        if (MODE == MERGE_ADAPTIVE) {
+            const float dsum = rows4_sum(distances(lo, k0));
+            inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
+        }
+        accumulate(lo, k0, v0);
+    } else {
+        E::to_float(kp_raw, kp);
+        if (MODE == MERGE_ADAPTIVE) {
+            // sweep 1: sum of the distances to the pivot
+            float dsum = 0.f;
+            for (int j0 = lo; j0 < hi; j0 += 4 * U) {
+                Raw kr[U];
+                load_rows(Ks, j0, kr);
+                dsum += distances(j0, kr);
+            }
+            dsum = rows4_sum(dsum);
+            inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
+        }
+        // sweep 2: weights and weighted sums (K again, now from L2; V for the first time)
+        for (int j0 = lo; j0 < hi; j0 += 4 * U) {
+            Raw kr[U], vr[U];
+            load_rows(Ks, j0, kr);
+            load_rows(Vs, j0, vr);
+            accumulate(j0, kr, vr);
+        }
+    }
+    gsum = rows4_sum(gsum);
+    const float inv_g = 1.f / gsum;
+    const float vscale = a.value_scale ? inv_g * (float)m : inv_g;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        ak[e] = rows4_sum(ak[e]) * inv_g;
+        av[e] = rows4_sum(av[e]) * vscale;
+    }
+    if (slot == 0) E::store(k_row, c, E::from_float(ak));
+    if (slot == 1) E::store(v_row, c, E::from_float(av));
+    if (WITH_W && c == 0) {                                        // each writer normalises its own g_j
+        for (int row = lo + slot; row < hi; row += 4) wo[row] *= inv_g;
+    }
+}
+
 template <typename T, bool WITH_W, int MODE>
 __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict__ K, const T *__restrict__ V,
                                                             T *__restrict__ K_out, T *__restrict__ V_out, MergeArgs a)
 {
     using E = Elem<T>;
     using Raw = typename E::Raw;
-    constexpr int U = MergeUnroll<T>::value;   // row groups (of 4 rows) in flight
-    constexpr int US = 4;                      // same for runs of singleton sets (16 = all of a wave's sets)
+    constexpr int US = 4;                      // row groups (of 4 rows) in flight in runs of singleton sets
     const int slice = blockIdx.x / a.tiles_per_slice;
     const int tile = blockIdx.x - slice * a.tiles_per_slice;
     const int lane = threadIdx.x & 63;
@@ -170,98 +288,8 @@ __global__ __launch_bounds__(MERGE_BLOCK) void merge_kernel(const T *__restrict_
         if (m <= 0 || m > LONG_SET_MIN) { ++i; continue; }                // inconsistent map: nothing to merge; long set: merge_long_kernel
         int p = __builtin_amdgcn_readlane(my_piv, i);
         p = min(max(p, lo), hi - 1);
-        const Raw kp_raw = E::load(Ks + (size_t)p * HEAD_DIM, c);
-        float kp[8];
-        float ak[8], av[8], gsum = 0.f, inv_mean = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { ak[e] = 0.f; av[e] = 0.f; }
-        // Rows past the end of the set are clamped to its last row and given weight zero, so
-        // that every lane runs the same straight-line code.
-        auto load_rows = [&](const T *base, int j0, Raw *r) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) r[u] = E::load(base + (size_t)min(j0 + 4 * u + slot, hi - 1) * HEAD_DIM, c);
-        };
-        auto distances = [&](int j0, const Raw *kr) {
-            float acc = 0.f;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float x[8];
-                E::to_float(kr[u], x);
-                const float dist = __builtin_amdgcn_sqrtf(sq_dist16(kp, x));
-                acc += (j0 + 4 * u + slot < hi) ? dist : 0.f;
-            }
-            return acc;
-        };
-        // g_j = exp(-D_j^2 / (2 sigma^2)); with sigma = dsum / (sqrt(2) m) that is exp(-(D_j m / dsum)^2)
-        auto accumulate = [&](int j0, const Raw *kr, const Raw *vr) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = j0 + 4 * u + slot;
-                float x[8], v[8];
-                E::to_float(kr[u], x);
-                float g;
-                if (MODE == MERGE_AVERAGE) {
-                    g = 1.f;
-                } else if (MODE == MERGE_FIXED) {
-                    g = __expf(-sq_dist16(kp, x) * a.inv_two_sigma_sq);
-                } else {
-                    const float r = __builtin_amdgcn_sqrtf(sq_dist16(kp, x)) * inv_mean;
-                    g = __expf(-r * r);
-                }
-                g = row < hi ? g : 0.f;
-                gsum += g;
-                E::to_float(vr[u], v);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { ak[e] = fmaf(g, x[e], ak[e]); av[e] = fmaf(g, v[e], av[e]); }
-                if (WITH_W && c == 0 && row < hi) wo[row] = g;
-            }
-        };
-
-        if (m <= 4 * U) {
-            // the whole set is read once: all loads issued together, both sweeps from registers
-            Raw k0[U], v0[U];
-            load_rows(Ks, lo, k0);
-            load_rows(Vs, lo, v0);
-            E::to_float(kp_raw, kp);
-            if (MODE == MERGE_ADAPTIVE) {
-                const float dsum = rows4_sum(distances(lo, k0));
-                inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
-            }
-            accumulate(lo, k0, v0);
-        } else {
-            E::to_float(kp_raw, kp);
-            if (MODE == MERGE_ADAPTIVE) {
-                // sweep 1: sum of the distances to the pivot
-                float dsum = 0.f;
-                for (int j0 = lo; j0 < hi; j0 += 4 * U) {
-                    Raw kr[U];
-                    load_rows(Ks, j0, kr);
-                    dsum += distances(j0, kr);
-                }
-                dsum = rows4_sum(dsum);
-                inv_mean = dsum > 0.f ? (float)m / dsum : 0.f;
-            }
-            // sweep 2: weights and weighted sums (K again, now from L2; V for the first time)
-            for (int j0 = lo; j0 < hi; j0 += 4 * U) {
-                Raw kr[U], vr[U];
-                load_rows(Ks, j0, kr);
-                load_rows(Vs, j0, vr);
-                accumulate(j0, kr, vr);
-            }
-        }
-        gsum = rows4_sum(gsum);
-        const float inv_g = 1.f / gsum;
-        const float vscale = a.value_scale ? inv_g * (float)m : inv_g;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            ak[e] = rows4_sum(ak[e]) * inv_g;
-            av[e] = rows4_sum(av[e]) * vscale;
-        }
-        if (slot == 0) E::store(Ko + (size_t)(s_lo + i) * HEAD_DIM, c, E::from_float(ak));
-        if (slot == 1) E::store(Vo + (size_t)(s_lo + i) * HEAD_DIM, c, E::from_float(av));
-        if (WITH_W && c == 0) {                                        // each writer normalises its own g_j
-            for (int row = lo + slot; row < hi; row += 4) wo[row] *= inv_g;
-        }
+        merge_one_set<T, WITH_W, MODE>(Ks, Vs, Ko + (size_t)(s_lo + i) * HEAD_DIM, Vo + (size_t)(s_lo + i) * HEAD_DIM, wo, lo, hi, p, a,
+                                       lane);
         ++i;
     }
 }
@@ -434,18 +462,6 @@ static void launch_merge_long_t(const kvm_shape &sh, const void *K, const void *
     }
 }
 
-// int32 entries of a slice's plan: tiles + 1 tile edges, the number of long sets, their indices
-static int merge_plan_stride(int N)
-{
-    const int tiles = (N + MERGE_TILE - 1) / MERGE_TILE;
-    return tiles + 2 + N / (LONG_SET_MIN + 1) + 1;
-}
-
-size_t merge_workspace_bytes(const kvm_shape &sh)
-{
-    return (size_t)sh.B * sh.H_kv * merge_plan_stride(sh.N) * sizeof(int32_t);
-}
-
 kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const int32_t *set_start, const int32_t *pivot, const int32_t *n_sets, void *K_out,
                         void *V_out, float *w_opt, int32_t *plan, hipStream_t st)
@@ -486,6 +502,223 @@ kvm_status launch_merge(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     default: launch_merge_long_t<bf16_t>(sh, K, V, K_out, V_out, a, st); break;
     }
     return check_launch("merge_long_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
+// Refresh of a compacted cache after the index maps changed a little (decode time: one more
+// token moves the recent window, the top-k and a few pivots).  A set of the new maps whose
+// extent and pivot already existed in the previous maps has the same merged row as before:
+// the row only moves to its new index; the others are merged again.  Result: bit for bit what
+// merge_kernel / merge_long_kernel give on the new maps.
+//
+// refresh_kernel, one 512-thread workgroup per slice, three phases with a barrier between them:
+//   compare   src[s] = row of the previous cache that new row s is (-1: merge again), the list
+//             of short sets to merge again, and the long ones in the layout merge_long_kernel
+//             reads (that kernel follows)
+//   move      rows in place.  src is increasing over the rows that move, so rows moving up
+//             never need a row that rows moving down overwrite and vice versa; rows moving up
+//             are taken from the top down, rows moving down from the bottom up, a batch at a time,
+//             all reads of a batch before its writes.
+//   merge     one wave per listed set (merge_one_set), the workgroup's waves in turn.  A
+//             slice that has little to move gets here early, so the longest set of the launch
+//             (one wave, up to LONG_SET_MIN rows) overlaps the other slices' moves.
+// ------------------------------------------------------------------------------------------
+
+struct RefreshArgs {
+    const int32_t *prev_set_id, *prev_set_start, *prev_pivot, *prev_n_sets;
+    int32_t *src;          // (slices, cap_rows)
+    int32_t *lists;        // (slices, cap_rows + 1): number of short sets to merge again, then their indices
+    int32_t *plan;         // what MergeArgs::plan points to; only the long-set part is filled
+    int32_t *n_changed;    // (slices) or NULL: sets merged again
+};
+
+constexpr int REFRESH_BLOCK = 512;                           // two workgroups per compute unit (128 registers each)
+template <typename T> struct MovePerGroup { static constexpr int value = 16 / sizeof(T); };   // rows a 16-lane group moves per batch
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(REFRESH_BLOCK, 4) void refresh_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                                T *__restrict__ K_out, T *__restrict__ V_out, MergeArgs a,
+                                                                RefreshArgs r)
+{
+    using E = Elem<T>;
+    using Raw = typename E::Raw;
+    constexpr int MOVE_PER_GROUP = MovePerGroup<T>::value;
+    constexpr int MOVE_BATCH = (REFRESH_BLOCK / 16) * MOVE_PER_GROUP;   // rows the workgroup moves per batch
+    __shared__ int n_short, n_long, first_moved, any_up, any_down;
+    const int slice = blockIdx.x;
+    const int tid = threadIdx.x, c = tid & 15, group = tid >> 4;
+    const int n = clamp_len(a.seq_lens, slice / a.H, a.N);
+    const int M = min(max(a.n_sets[slice], 0), a.cap_rows);
+    const int M_old = min(max(r.prev_n_sets[slice], 0), a.cap_rows);
+    const int32_t *sst = a.set_start + (size_t)slice * (a.cap_rows + 1);
+    const int32_t *piv = a.pivot + (size_t)slice * a.cap_rows;
+    const int32_t *osst = r.prev_set_start + (size_t)slice * (a.cap_rows + 1);
+    const int32_t *opiv = r.prev_pivot + (size_t)slice * a.cap_rows;
+    const int32_t *osid = r.prev_set_id + (size_t)slice * a.N;
+    int32_t *src = r.src + (size_t)slice * a.cap_rows;
+    int32_t *list = r.lists + (size_t)slice * (a.cap_rows + 1);
+    int32_t *pl = r.plan + (size_t)slice * a.plan_stride + a.tiles_per_slice + 1;
+    const int max_long = a.plan_stride - (a.tiles_per_slice + 2);
+    T *Ko = K_out + (size_t)slice * a.cap_rows * HEAD_DIM;
+    T *Vo = V_out + (size_t)slice * a.cap_rows * HEAD_DIM;
+
+    // ---- compare ------------------------------------------------------------------------------
+    if (tid == 0) { n_short = 0; n_long = 0; first_moved = M; any_up = 0; any_down = 0; }
+    __syncthreads();
+    int my_first = M;
+    bool my_up = false, my_down = false;
+    for (int s = tid; s < M; s += REFRESH_BLOCK) {
+        const int lo = min(max(sst[s], 0), n), hi = min(max(sst[s + 1], 0), n);
+        int from = -1;
+        if (hi > lo) {
+            const int so = osid[lo];                          // the previous set of the new set's first token
+            if (so >= 0 && so < M_old && osst[so] == sst[s] && osst[so + 1] == sst[s + 1] && opiv[so] == piv[s]) from = so;
+        }
+        src[s] = from;
+        if (from < 0) {
+            if (hi - lo > LONG_SET_MIN) {
+                const int k = atomicAdd(&n_long, 1);
+                if (k < max_long) pl[1 + k] = s;
+            } else {
+                list[1 + atomicAdd(&n_short, 1)] = s;
+            }
+        } else if (from != s) {
+            my_first = min(my_first, s);
+            my_up |= from < s;
+            my_down |= from > s;
+        }
+    }
+    if (my_first < M) atomicMin(&first_moved, my_first);
+    if (my_up) any_up = 1;
+    if (my_down) any_down = 1;
+    __syncthreads();                                          // src and list are read below by other threads of this workgroup
+    const int first = first_moved;
+    const bool moves_up = any_up != 0, moves_down = any_down != 0;
+    const int cnt = n_short;
+    if (tid == 0) {
+        list[0] = cnt;
+        pl[0] = min(n_long, max_long);
+        if (r.n_changed) r.n_changed[slice] = cnt + n_long;
+    }
+
+    // ---- move ---------------------------------------------------------------------------------
+    // (a direction that no row takes is skipped as a whole: after one more token nearly all rows
+    // that move go the same way)
+    const int b_lo = first / MOVE_BATCH, b_hi = (M - 1) / MOVE_BATCH;
+    int s[MOVE_PER_GROUP], f[MOVE_PER_GROUP], f_next[MOVE_PER_GROUP];
+    Raw rk[MOVE_PER_GROUP], rv[MOVE_PER_GROUP];
+    auto sources = [&](int bt, int *out) {                    // the batch's sources, before the direction filter
+#pragma unroll
+        for (int u = 0; u < MOVE_PER_GROUP; ++u) {
+            const int row = bt * MOVE_BATCH + u * (REFRESH_BLOCK / 16) + group;
+            out[u] = row < M ? src[row] : -1;
+        }
+    };
+    auto move_batch = [&](int bt, bool up, int bt_next, bool more) {
+        bool any = false;
+#pragma unroll
+        for (int u = 0; u < MOVE_PER_GROUP; ++u) {
+            s[u] = bt * MOVE_BATCH + u * (REFRESH_BLOCK / 16) + group;
+            f[u] = f_next[u];
+            if (!(up ? (f[u] >= 0 && f[u] < s[u]) : f[u] > s[u])) f[u] = -1;
+            any |= f[u] >= 0;
+        }
+        if (more) sources(bt_next, f_next);                   // in flight across the barriers
+        if (!__syncthreads_or(any ? 1 : 0)) return;
+#pragma unroll
+        for (int u = 0; u < MOVE_PER_GROUP; ++u)
+            if (f[u] >= 0) { rk[u] = E::load(Ko + (size_t)f[u] * HEAD_DIM, c); rv[u] = E::load(Vo + (size_t)f[u] * HEAD_DIM, c); }
+        __syncthreads();                                      // every source row of the batch is in registers
+#pragma unroll
+        for (int u = 0; u < MOVE_PER_GROUP; ++u)
+            if (f[u] >= 0) { E::store(Ko + (size_t)s[u] * HEAD_DIM, c, rk[u]); E::store(Vo + (size_t)s[u] * HEAD_DIM, c, rv[u]); }
+    };
+    if (moves_up) {                                           // new index above the old one: batches from the top down
+        sources(b_hi, f_next);
+        for (int bt = b_hi; bt >= b_lo; --bt) move_batch(bt, true, bt - 1, bt > b_lo);
+    }
+    if (moves_up && moves_down) __syncthreads();
+    if (moves_down) {                                         // batches from the bottom up
+        sources(b_lo, f_next);
+        for (int bt = b_lo; bt <= b_hi; ++bt) move_batch(bt, false, bt + 1, bt < b_hi);
+    }
+    if (moves_up || moves_down) __syncthreads();              // a row merged below may be one that was a source above
+
+    // ---- merge the listed sets again -------------------------------------------------------------
+    const int lane = tid & 63;
+    const T *Ks = K + (size_t)slice * a.N * HEAD_DIM;
+    const T *Vs = V + (size_t)slice * a.N * HEAD_DIM;
+    for (int k = tid >> 6; k < cnt; k += REFRESH_BLOCK / WAVE) {
+        const int s = list[1 + k];
+        if (s < 0 || s >= M) continue;                        // (the same for the whole wave)
+        const int lo = min(max(sst[s], 0), n), hi = min(max(sst[s + 1], 0), n);
+        if (hi - lo <= 0 || hi - lo > LONG_SET_MIN) continue;
+        const int p = min(max(piv[s], lo), hi - 1);
+        merge_one_set<T, false, MODE>(Ks, Vs, Ko + (size_t)s * HEAD_DIM, Vo + (size_t)s * HEAD_DIM, nullptr, lo, hi, p, a, lane);
+    }
+}
+
+template <typename T>
+static kvm_status launch_refresh_t(const kvm_shape &sh, const void *K, const void *V, void *K_out, void *V_out,
+                                   const MergeArgs &ma, const RefreshArgs &ra, hipStream_t st)
+{
+    const dim3 grid((unsigned)((long long)sh.B * sh.H_kv)), block(REFRESH_BLOCK);
+    {
+        ProfScope prof("refresh_kernel", st);
+        const T *k = (const T *)K, *v = (const T *)V;
+        T *ko = (T *)K_out, *vo = (T *)V_out;
+        if (ma.mode == MERGE_AVERAGE) hipLaunchKernelGGL((refresh_kernel<T, MERGE_AVERAGE>), grid, block, 0, st, k, v, ko, vo, ma, ra);
+        else if (ma.mode == MERGE_FIXED) hipLaunchKernelGGL((refresh_kernel<T, MERGE_FIXED>), grid, block, 0, st, k, v, ko, vo, ma, ra);
+        else hipLaunchKernelGGL((refresh_kernel<T, MERGE_ADAPTIVE>), grid, block, 0, st, k, v, ko, vo, ma, ra);
+    }
+    kvm_status rc = check_launch("refresh_kernel");
+    if (rc != KVM_OK || sh.N <= LONG_SET_MIN) return rc;
+    launch_merge_long_t<T>(sh, K, V, K_out, V_out, ma, st);
+    return check_launch("merge_long_kernel");
+}
+
+size_t merge_refresh_workspace_bytes(const kvm_shape &sh, int cap_rows)
+{
+    return (size_t)sh.B * sh.H_kv * ((size_t)merge_plan_stride(sh.N) + 2 * (size_t)cap_rows + 1) * sizeof(int32_t);
+}
+
+kvm_status launch_merge_refresh(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
+                                const int32_t *prev_set_id, const int32_t *prev_set_start, const int32_t *prev_pivot,
+                                const int32_t *prev_n_sets, const int32_t *set_start, const int32_t *pivot,
+                                const int32_t *n_sets, void *K_out, void *V_out, int32_t *n_changed, int32_t *ws, hipStream_t st)
+{
+    const size_t slices = (size_t)sh.B * sh.H_kv;
+    if (slices == 0 || cap_rows == 0 || sh.N == 0) return KVM_OK;
+    const int plan_stride = merge_plan_stride(sh.N);
+    RefreshArgs ra;
+    ra.prev_set_id = prev_set_id;
+    ra.prev_set_start = prev_set_start;
+    ra.prev_pivot = prev_pivot;
+    ra.prev_n_sets = prev_n_sets;
+    ra.src = ws + slices * plan_stride;
+    ra.lists = ra.src + slices * cap_rows;
+    ra.plan = ws;
+    ra.n_changed = n_changed;
+    MergeArgs ma;
+    ma.set_start = set_start;
+    ma.pivot = pivot;
+    ma.n_sets = n_sets;
+    ma.seq_lens = sh.seq_lens;
+    ma.w_opt = nullptr;
+    ma.plan = ws;
+    ma.plan_stride = plan_stride;
+    ma.H = sh.H_kv;
+    ma.N = sh.N;
+    ma.cap_rows = cap_rows;
+    ma.tiles_per_slice = (sh.N + MERGE_TILE - 1) / MERGE_TILE;
+    ma.mode = pr.weights == KVM_WEIGHTS_AVERAGE ? MERGE_AVERAGE : (pr.sigma_mode == KVM_SIGMA_FIXED ? MERGE_FIXED : MERGE_ADAPTIVE);
+    ma.inv_two_sigma_sq = ma.mode == MERGE_FIXED ? 1.f / (2.f * pr.sigma * pr.sigma) : 0.f;
+    ma.value_scale = pr.value_scale_by_set_size;
+    switch (sh.dtype) {
+    case KVM_F32: return launch_refresh_t<float>(sh, K, V, K_out, V_out, ma, ra, st);
+    case KVM_F16: return launch_refresh_t<half_t>(sh, K, V, K_out, V_out, ma, ra, st);
+    default: return launch_refresh_t<bf16_t>(sh, K, V, K_out, V_out, ma, ra, st);
+    }
 }
 
 // ------------------------------------------------------------------------------------------

@@ -158,6 +158,19 @@ def test_host_detectable_errors_return_before_any_launch():
     assert merge_static(_shape(B=2 ** 10, H_kv=2 ** 6, N=2 ** 17), p) == kb.KVM_ERR_WORKSPACE
     assert b"built-in buffer" in lib.kvm_last_error()
 
+    two = ctypes.c_void_p(32)
+
+    def refresh(sh, pr, K=one, new=two, ws=one, nbytes=1 << 30):
+        return lib.kvm_merge_refresh(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, new, new, new, one, one, None,
+                                     ws, nbytes, None)
+
+    assert refresh(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
+    assert refresh(_shape(), p, new=one) == kb.KVM_ERR_INVALID_ARG and b"different buffers" in lib.kvm_last_error()
+    assert refresh(_shape(d=256), p) == kb.KVM_ERR_UNSUPPORTED
+    assert refresh(_shape(), p, ws=None) == kb.KVM_ERR_WORKSPACE
+    assert refresh(_shape(), p, nbytes=4) == kb.KVM_ERR_WORKSPACE
+    assert refresh(_shape(N=0), p, K=None) == kb.KVM_OK                           # nothing to do
+
 
 def test_binding_refuses_mismatched_tensors_on_the_host():
     import torch

@@ -708,6 +708,103 @@ def test_merge_tolerates_inconsistent_maps():
     assert np.isfinite(ko).all() and np.isfinite(vo).all()
 
 
+@pytest.mark.parametrize("dtype,mode", [("f16", "gaussian"), ("bf16", "fixed_sigma"), ("f32", "average")])
+def test_merge_refresh_over_decode_steps(dtype, mode):
+    """Decode-time loop on a growing sequence: scores updated by one query row, one new similarity,
+    sets identified again, and the compacted cache brought up to date by kvm_merge_refresh (rows of
+    unchanged sets moved, the others merged again).  After every one of 20 steps the cache must be,
+    bit for bit, what kvm_merge gives on the new maps; the last one is also held against the oracle.
+    The second batch row is 300 tokens shorter and one slice has a run of identical keys, i.e. a set
+    long enough for the workgroup-per-set kernel that keeps growing."""
+    n0, steps, N = 1500, 20, 1536
+    n1 = n0 + steps
+    lens1 = [n1, n1 - 300]
+    _say(f"merge refresh over decode steps {n0}..{n1}, {dtype}, {mode}")
+    Q, K, V = _slices(41, 2, 2, lens1, N, 128, 1, dtype)
+    K[0, 1, 200:n1] = K[0, 1, 200]                         # one long run of identical keys, up to the newest token
+    params = kb.kvm_params_for_budget(0.5)
+    if mode == "fixed_sigma":
+        params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, 4.0
+    elif mode == "average":
+        params.weights = kb.KVM_WEIGHTS_AVERAGE
+    Qd, Kd, Vd = gu.to_dev(Q, dtype), gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+    tdt = gu.TORCH_DT[dtype]
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def shape_at(lens):
+        sl = gu.lens_dev(lens)
+        return kb.make_shape(Kd, 1, sl)
+
+    sh = shape_at([n0, n0 - 300])
+    cap = kb.kvm_out_capacity(sh, params)
+    ws = torch.empty(max(kb.kvm_workspace_bytes(sh, params), 256), dtype=torch.uint8, device="cuda")
+    mass = torch.empty((2, 2, N), dtype=torch.float32, device="cuda")
+    sim = torch.empty((2, 2, N), dtype=torch.float32, device="cuda")
+    maps = [dict(set_id=torch.full((2, 2, N), -7, **i32), set_start=torch.full((2, 2, cap + 1), -7, **i32),
+                 pivot=torch.full((2, 2, cap), -7, **i32), n_sets=torch.full((2, 2), -7, **i32),
+                 status=torch.full((2, 2), -7, **i32)) for _ in range(2)]
+    Ko = torch.zeros((2, 2, cap, 128), dtype=tdt, device="cuda")
+    Vo = torch.zeros_like(Ko)
+    n_changed = torch.full((2, 2), -1, **i32)
+
+    def identify(sh, m, given):
+        params.sim_given = 1 if given else 0
+        kb.kvm_identify_sets(sh, params, Kd, mass, m["set_id"], m["set_start"], m["pivot"], m["n_sets"], sim, m["status"], ws)
+
+    # prefill: the whole pass once
+    kb.kvm_attn_mass(sh, Qd, Kd, mass, ws)
+    identify(sh, maps[0], False)
+    kb.kvm_merge(sh, params, Kd, Vd, maps[0]["set_start"], maps[0]["pivot"], maps[0]["n_sets"], Ko, Vo, None, ws)
+    cur = 0
+    total_changed = 0
+    bits = torch.int32 if dtype == "f32" else torch.int16
+    for step in range(1, steps + 1):
+        lens = [n0 + step, n0 + step - 300]
+        sh = shape_at(lens)
+        q_new = torch.stack([Qd[b, :, n - 1] for b, n in enumerate(lens)]).contiguous()
+        kb.kvm_attn_mass_append(sh, q_new, Kd, mass, ws)
+        kb.kvm_sim_append(sh, Kd, sim)
+        new = 1 - cur
+        identify(sh, maps[new], True)
+        kb.kvm_merge_refresh(sh, params, Kd, Vd, maps[cur]["set_id"], maps[cur]["set_start"], maps[cur]["pivot"],
+                             maps[cur]["n_sets"], maps[new]["set_start"], maps[new]["pivot"], maps[new]["n_sets"], Ko, Vo,
+                             n_changed, ws)
+        Kf = torch.zeros_like(Ko)
+        Vf = torch.zeros_like(Vo)
+        kb.kvm_merge(sh, params, Kd, Vd, maps[new]["set_start"], maps[new]["pivot"], maps[new]["n_sets"], Kf, Vf, None, ws)
+        torch.cuda.synchronize()
+        ns = maps[new]["n_sets"].cpu().numpy()
+        for b in range(2):
+            for h in range(2):
+                M = min(int(ns[b, h]), cap)
+                assert torch.equal(Ko[b, h, :M].view(bits), Kf[b, h, :M].view(bits)), f"step {step} slice ({b},{h}): K rows differ"
+                assert torch.equal(Vo[b, h, :M].view(bits), Vf[b, h, :M].view(bits)), f"step {step} slice ({b},{h}): V rows differ"
+        ch = n_changed.cpu().numpy()
+        assert (ch >= 1).all() and (ch <= ns).all()          # the set that holds the newest token is always new
+        total_changed += int(ch.sum())
+        cur = new
+    _say(f"  sets merged again per step and slice: {total_changed / (steps * 4):.1f} of about {int(ns.mean())}")
+    assert total_changed < 0.2 * steps * ns.sum()            # the point of the call: most rows are kept
+    # the final state against the oracle: maps from the library's own scores, merged rows to the merge bar
+    params.sim_given = 0
+    m_g = mass.cpu().numpy()
+    o = ref.identify_sets(K, m_g.astype(np.float64), dtype, params.budget, params.recent_ratio, params.heavy_ratio,
+                          params.threshold, True, cap, lens1)
+    g = {k: v.cpu().numpy() for k, v in maps[cur].items()}
+    g["cap_rows"] = cap
+    exc, _ = gu.compare_maps(g, o, lens1, N, params.threshold, "refresh, final maps")
+    assert exc == 0
+    rk, rv, _ = ref.merge(K, V, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
+                          bool(params.value_scale_by_set_size), lens1, weights=params.weights)
+    for b in range(2):
+        for h in range(2):
+            M = min(int(o["n_sets"][b, h]), cap)
+            assert gu.row_rel_err(gu.to_host_f64(Ko[b, h, :M]), rk[b, h, :M]).max() <= gu.kv_tol(dtype)
+            assert gu.row_rel_err(gu.to_host_f64(Vo[b, h, :M]), rv[b, h, :M]).max() <= gu.kv_tol(dtype)
+            assert gu.ulp_excess(gu.to_host_f64(Ko[b, h, :M]), rk[b, h, :M], dtype).max() <= 2e-5
+            assert gu.ulp_excess(gu.to_host_f64(Vo[b, h, :M]), rv[b, h, :M], dtype).max() <= 2e-5
+
+
 # ---------------------------------------------------------------------------------------------
 # whole pass
 # ---------------------------------------------------------------------------------------------
