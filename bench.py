@@ -24,15 +24,43 @@ PEAK_MFMA = {"f16": 2.5e15, "bf16": 2.5e15, "f32": 157.3e12}   # dense matrix pe
 PEAK_HBM = 8.0e12                                               # B/s
 METRIC = "KV tokens compressed/sec (all layers x heads) at Llama2-7B N=4096"
 
-# HBM bytes per launch (read, written) on the headline workload (--config 2, all layers, budget 0.5),
-# from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (hardware counters cannot
-# be read from inside this process; re-measure after a kernel change).
-MEASURED_TRAFFIC = {
-    "attn_lse_kernel": (2698233226, 25400330),
-    "attn_colsum_kernel": (2838583327, 159376384),
-    "cosine_scan_kernel": (1077733889, 18364522),
-    "merge_kernel": (2672580229, 676896256),
-}
+def kernel_sources_sha256() -> str:
+    """Hash of the HIP sources the library is built from: the stamp of the counter measurements under profiles/."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2407_08454_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str) -> dict:
+    """{kernel: (bytes fetched, bytes written) per launch} from profiles/hbm_traffic_<workload>.md (FETCH_SIZE /
+    WRITE_SIZE counter runs; hardware counters cannot be read from inside this process).  Empty when the file is
+    missing or was measured on other kernel sources than the ones in the tree: the figures would be stale."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.md")
+    if not os.path.exists(path):
+        return {}
+    out, stamp = {}, None
+    for line in open(path):
+        if line.startswith("sources_sha256:"):
+            stamp = line.split(":", 1)[1].strip()
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 3 and cells[0].endswith("_kernel") and cells[1].isdigit() and cells[2].isdigit():
+            out[cells[0]] = (int(cells[1]), int(cells[2]))
+    return out if stamp == kernel_sources_sha256() else {}
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main() -> int:
@@ -126,19 +154,34 @@ def main() -> int:
 
     append = args.method == "append"
     if append:
-        # the prompt's scores once, untimed; every step then treats the last token as newly arrived
-        variant += "; decode-time refresh (one query row per step, then sets and merge)"
-        q_new = Qd[:, :, N - 1].contiguous() if lens is None else torch.stack(
-            [Qd[b, :, max(int(n) - 1, 0)] for b, n in enumerate(lens)]).contiguous()
+        # Decode-time loop on a growing sequence: the prompt is the workload minus the tokens that the
+        # warm-up and timed steps append; its whole pass runs once, untimed.  Every step then appends one
+        # token: one query row added to the scores, one new similarity, sets identified again (similarities
+        # carried), and the compacted cache brought up to date (kvm_merge_refresh).
+        variant += "; decode-time refresh (per token: one query row, one similarity, sets, cache refresh)"
+        grow = args.warmup + args.steps
+        if lens is not None or grow >= N:
+            print("bench.py: --method append needs a workload of equal lengths longer than warmup + steps", file=sys.stderr)
+            return 2
+        sl = torch.full((B,), N - grow, dtype=torch.int32, device="cuda")
+        shape = kb.make_shape(Kd, G, sl)
         kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
-        # the similarities are carried from call to call: all of them once, then one per step
         sim_carried = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
-        kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
-                             buf.status, buf.ws)
+        maps = [(buf.set_id, buf.set_start, buf.pivot, buf.n_sets),
+                tuple(torch.empty_like(t) for t in (buf.set_id, buf.set_start, buf.pivot, buf.n_sets))]
+        cur = [0]
+        kb.kvm_identify_sets(shape, params, Kd, buf.mass, *maps[0], sim_carried, buf.status, buf.ws)
+        kb.kvm_merge(shape, params, Kd, Vd, maps[0][1], maps[0][2], maps[0][3], buf.K_out, buf.V_out, None, buf.ws)
         params.sim_given = 0 if args.sets == "anchor" else 1       # the anchor rule needs the key norms of a scan
+        n_now = [N - grow]
+        # the appended tokens' query rows, one contiguous (B, H G, d) block per step
+        q_steps = Qd[:, :, N - grow:N].permute(2, 0, 1, 3).contiguous()
 
     def attn_mass():
         if append:
+            sl.add_(1)                                          # the token's key and value are already in K, V
+            n_now[0] += 1
+            q_new = q_steps[n_now[0] - 1 - (N - grow)]
             kb.kvm_attn_mass_append(shape, q_new, Kd, buf.mass, buf.ws)
             kb.kvm_sim_append(shape, Kd, sim_carried)
         elif row_lse is None:
@@ -153,15 +196,29 @@ def main() -> int:
         def rest():
             kb.kvm_evict(shape, params, Kd, Vd, buf.mass, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.ws)
         buf.status.zero_()
+    def identify():
+        if append:
+            new = maps[1 - cur[0]]
+            kb.kvm_identify_sets(shape, params, Kd, buf.mass, *new, sim_carried, buf.status, buf.ws)
+        else:
+            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
+                                 buf.status, buf.ws)
+
+    def merge():
+        if append:
+            old, new = maps[cur[0]], maps[1 - cur[0]]
+            kb.kvm_merge_refresh(shape, params, Kd, Vd, *old, new[1], new[2], new[3], buf.K_out, buf.V_out, None, buf.ws)
+            cur[0] = 1 - cur[0]
+        else:
+            kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None, buf.ws)
+
     for _ in range(args.warmup):
         attn_mass()
         if evict:
             rest()
         else:
-            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
-                                 buf.status, buf.ws)
-            kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None,
-                         buf.ws)
+            identify()
+            merge()
     torch.cuda.synchronize()
     if args.calibration_copy:          # reads and writes K.numel() * element_size bytes exactly once
         copy = torch.empty_like(Kd)
@@ -170,7 +227,7 @@ def main() -> int:
         del copy
 
     if not args.no_profile:
-        kb.kvm_profile_enable(8 * args.steps)
+        kb.kvm_profile_enable(12 * args.steps)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -182,11 +239,9 @@ def main() -> int:
             e[2].record()
             rest()
         else:
-            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
-                                 buf.status, buf.ws)
+            identify()
             e[2].record()
-            kb.kvm_merge(shape, params, Kd, Vd, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, None,
-                         buf.ws)
+            merge()
         e[3].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -197,7 +252,7 @@ def main() -> int:
         kernels = {k: v[1] / max(v[0], 1) for k, v in kb.kvm_profile_collect().items()}
         kb.kvm_profile_disable()
 
-    n_sets = buf.n_sets.cpu().numpy().astype(np.int64)
+    n_sets = (maps[cur[0]][3] if append else buf.n_sets).cpu().numpy().astype(np.int64)
     status = buf.status.cpu().numpy()
     M_total = int(n_sets.sum())
 
@@ -214,8 +269,10 @@ def main() -> int:
     headline = (args.keys == "ar1" and args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
                 and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None)
 
+    counters = measured_traffic("llama2-7b_n4096_f16") if headline else {}
+
     def traffic(name):
-        return float(sum(MEASURED_TRAFFIC[name])) if headline and name in MEASURED_TRAFFIC else None
+        return float(sum(counters[name])) if name in counters else None
 
     if kernels:
         dom = max(kernels, key=kernels.get)
@@ -238,42 +295,82 @@ def main() -> int:
                              "GB/s": byts / (kernels[name] * 1e-3) / 1e9,
                              "frac_of_hbm_peak": byts / (kernels[name] * 1e-3) / PEAK_HBM}
 
+    # the stages as wholes: stage (a) counted once (one causal QK^T is the method's work, both score passes are
+    # charged to it), stages (b)+(c) together against the bytes they have to move
+    # (K twice, V once, merged rows, scores, similarities and maps: 3 n d s + 2 M d s + 20 n per slice)
+    stage_fractions = None
+    if not append and not evict and stage_ms[0] > 0:
+        bytes_bc = float(3 * token_slices * d * esz + 2 * M_total * d * esz + 20 * token_slices)
+        stage_fractions = {
+            "attn_mass_of_mfma_peak": flops_attn / (stage_ms[0] / args.steps * 1e-3) / PEAK_MFMA[dtype],
+            "identify_plus_merge_of_hbm_peak": bytes_bc / ((stage_ms[1] + stage_ms[2]) / args.steps * 1e-3) / PEAK_HBM,
+            "identify_plus_merge_algorithmic_GB": bytes_bc / 1e9,
+        }
+
     # ---- the oracle on the host cores, on a sample of the same slices --------------------------
     cpu = None
     if args.cpu_slices > 0 and evict:
         print("bench.py: no CPU baseline leg for --method evict (use --cpu-slices 0)", file=sys.stderr)
     if args.cpu_slices > 0 and not evict:
         from oracle import ref
+
+        def oracle_pass(S):
+            """The oracle's whole pass (or one decode-time refresh) on S slices spread over layers and heads."""
+            idx = np.linspace(0, B * H - 1, S).astype(int)
+            Ks = np.ascontiguousarray(K.reshape(B * H, N, d)[idx])[:, None]
+            Vs = np.ascontiguousarray(V.reshape(B * H, N, d)[idx])[:, None]
+            Qs = np.ascontiguousarray(Q.reshape(B * H, G, N, d)[idx])
+            ls = None if lens is None else lens[idx // H]
+            t0 = time.perf_counter()
+            if append:
+                # scores before the step: seeded positive numbers (the oracle's time does not depend on them)
+                m0 = np.random.default_rng(0).random((S, 1, N)) + 0.01
+                qn = np.ascontiguousarray(Qs[:, :, N - 1] if ls is None else
+                                          np.stack([Qs[i, :, max(int(n) - 1, 0)] for i, n in enumerate(ls)]))
+                m = ref.attn_mass_append(qn, Ks, m0, dtype, G=G, seq_lens=ls)
+            else:
+                m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
+            o = ref.identify_sets(Ks, m.astype(np.float32).astype(np.float64), dtype, params.budget, params.recent_ratio,
+                                  params.heavy_ratio, params.threshold, True, buf.cap, ls, pivot_rule=params.pivot_rule,
+                                  pivot_seed=params.pivot_seed, set_rule=params.set_rule)
+            ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
+                      bool(params.value_scale_by_set_size), seq_lens=ls, weights=params.weights)
+            secs = time.perf_counter() - t0
+            toks = S if append else int(N * S if ls is None else ls.sum())
+            return toks / secs, secs
+
+        what = "one decode-time refresh" if append else "whole pass"
         S = min(args.cpu_slices, B * H)
-        idx = np.linspace(0, B * H - 1, S).astype(int)          # spread over layers and heads
-        Ks = np.ascontiguousarray(K.reshape(B * H, N, d)[idx])[:, None]
-        Vs = np.ascontiguousarray(V.reshape(B * H, N, d)[idx])[:, None]
-        Qs = np.ascontiguousarray(Q.reshape(B * H, G, N, d)[idx])
-        ls = None if lens is None else lens[idx // H]
-        t0 = time.perf_counter()
-        if append:
-            # scores before the step: seeded positive numbers (the oracle's time does not depend on them)
-            m0 = np.random.default_rng(0).random((S, 1, N)) + 0.01
-            qn = np.ascontiguousarray(Qs[:, :, N - 1] if ls is None else
-                                      np.stack([Qs[i, :, max(int(n) - 1, 0)] for i, n in enumerate(ls)]))
-            m = ref.attn_mass_append(qn, Ks, m0, dtype, G=G, seq_lens=ls)
-        else:
-            m = ref.attn_mass(Qs, Ks, dtype, G=G, seq_lens=ls)
-        o = ref.identify_sets(Ks, m.astype(np.float32).astype(np.float64), dtype, params.budget, params.recent_ratio,
-                              params.heavy_ratio, params.threshold, True, buf.cap, ls, pivot_rule=params.pivot_rule,
-                              pivot_seed=params.pivot_seed, set_rule=params.set_rule)
-        ref.merge(Ks, Vs, dtype, o["set_start"], o["pivot"], o["n_sets"], params.sigma_mode, params.sigma,
-                  bool(params.value_scale_by_set_size), seq_lens=ls, weights=params.weights)
-        cpu_s = time.perf_counter() - t0
-        toks = S if append else int(N * S if ls is None else ls.sum())
         cores = ref.num_threads()
-        cpu = {"value": toks / cpu_s, "unit": "token-slices/s", "cores": cores, "kind": "oracle",
-               "sample": f"{S} of {B * H} slices (evenly spaced over layers and heads), {'one decode-time refresh' if append else 'whole pass'} in fp64, "
-                         f"{cpu_s:.1f} s wall on {cores} OpenMP threads"}
+        rate, secs = oracle_pass(S)
+        cpu = {"value": rate, "unit": "token-slices/s", "cores": cores, "kind": "oracle", "cpu_model": cpu_model(),
+               "sample": f"{S} of {B * H} slices (evenly spaced over layers and heads), {what} in fp64, "
+                         f"{secs:.1f} s wall on {cores} OpenMP threads"}
+        # the same on one core, on a sample cut down by the core count so that it takes about as long
+        S1 = max(1, min(S, S // max(cores, 1)))
+        ref.set_num_threads(1)
+        rate1, secs1 = oracle_pass(S1)
+        ref.set_num_threads(cores)
+        cpu["single_core"] = {"value": rate1, "unit": "token-slices/s", "cores": 1,
+                              "sample": f"{S1} of {B * H} slices, {what} in fp64, {secs1:.1f} s wall on one thread"}
 
     metric, work = METRIC, token_slices
+    refresh = None
     if append:                                              # one token per slice and step
         metric, work = "decode-time refresh: appended tokens/sec (all layers x heads) at Llama2-7B N=4096", B * H
+        # what the last step's refresh had to do: sets merged again, kept rows whose index changed
+        o_sid, o_st, o_pv, o_ns = (t.cpu().numpy().reshape(B * H, -1) for t in maps[1 - cur[0]])
+        _, n_st, n_pv, n_ns = (t.cpu().numpy().reshape(B * H, -1) for t in maps[cur[0]])
+        again = moved = 0
+        for i in range(B * H):
+            M, Mo = int(n_ns[i, 0]), int(o_ns[i, 0])
+            lo, hi, pv = n_st[i, :M], n_st[i, 1:M + 1], n_pv[i, :M]
+            so = np.clip(o_sid[i, lo], 0, max(Mo - 1, 0))
+            same = (o_st[i, so] == lo) & (o_st[i, so + 1] == hi) & (o_pv[i, so] == pv)
+            again += int((~same).sum())
+            moved += int((same & (so != np.arange(M))).sum())
+        refresh = {"sets_merged_again_per_slice": again / (B * H), "rows_moved_per_slice": moved / (B * H),
+                   "rows_per_slice": M_total / (B * H), "moved_GB": 4.0 * moved * d * esz / 1e9}
     out = {
         "metric": metric, "value": work / (ms_per_step * 1e-3), "unit": "token-slices/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -286,11 +383,13 @@ def main() -> int:
                    "M_over_n_per_layer": [round(float(x), 4) for x in
                                           (n_sets.reshape(-1, cfg["batch"], H).sum((1, 2)) /
                                            (n_per_b.reshape(-1, cfg["batch"]).sum(1) * H))]},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "stage_fractions": stage_fractions,
         "stage_ms": {"attn_mass": stage_ms[0] / args.steps, "identify_sets": stage_ms[1] / args.steps,
                      "merge": stage_ms[2] / args.steps},
         "kernel_ms": kernels, "hbm_kernels": hbm, "input_generation_s": gen_s,
     }
+    if refresh is not None:
+        out["last_refresh"] = refresh
     print(json.dumps(out))
     return 0
 
