@@ -43,6 +43,10 @@
  *         values in (0,1]).  PARITY UNPINNED against the authors' own code.
  *   R-c3  sigma == 0 (all keys of the set equal the pivot) gives g = 1.
  *   R-c4  value weights are the key weights times |S| (Section 4.2), optional.
+ *   R-v   (comparison workload only) value-only merging, of which Section 2.3 gives one
+ *         sentence: evicted values go to the kept token nearest by position (a tie to the
+ *         later one) and the kept value becomes the plain mean.  PARITY UNPINNED against
+ *         the scheme's own publication, which is not in the paper.
  *
  * Variants the paper studies (Section 4.2 first experiment, Section 5.4), selectable here:
  *   - average weighted merging: every member of a set gets weight 1/|S|
@@ -613,6 +617,49 @@ int kvm_ref_evict(int B, int H, int N, int d, int dtype, const int32_t *seq_lens
         for (j = m; j < cap_rows; ++j) kept[(size_t)bh * cap_rows + j] = -1;
         n_kept[bh] = m;
         free(keep); free(rk); free(row);
+    }
+    return 0;
+}
+
+/*
+ * A second comparison workload: value-only merging.  Section 2.3 says of the value-merging
+ * scheme the paper compares with only that it merges the value states about to be evicted into
+ * the conserved ones.  Reading built here: the selection is the eviction policy above; the keys
+ * of evicted tokens are dropped; every evicted token's value goes to the kept token nearest to
+ * it by position (equal distances: the later one), and a kept token's new value is the plain
+ * mean of its own value and the values that went to it.  Same outputs as kvm_ref_evict, V_out
+ * holding the means; count_opt (B, H, cap_rows), may be NULL: how many values each mean covers.
+ */
+int kvm_ref_evict_merge_values(int B, int H, int N, int d, int dtype, const int32_t *seq_lens, double budget,
+                               double recent_ratio, int cap_rows, const void *K, const void *V, const double *mass,
+                               int32_t *kept, int32_t *n_kept, double *K_out, double *V_out, int32_t *count_opt)
+{
+    int bh, rc;
+    rc = kvm_ref_evict(B, H, N, d, dtype, seq_lens, budget, recent_ratio, cap_rows, K, V, mass, kept, n_kept, K_out, V_out);
+    if (rc) return rc;
+    for (bh = 0; bh < B * H; ++bh) {
+        int n = valid_len(seq_lens, bh / H, N);
+        int m = n_kept[bh], j, s, e;
+        const int32_t *pos = kept + (size_t)bh * cap_rows;
+        double *sum = (double *)calloc((size_t)(m > 0 ? m : 1) * (size_t)d, sizeof(double));
+        int *cnt = (int *)calloc((size_t)(m > 0 ? m : 1), sizeof(int));
+        double *row = (double *)malloc(sizeof(double) * (size_t)d);
+        for (j = 0; j < n && m > 0; ++j) {
+            int best = 0;
+            for (s = 1; s < m; ++s) {                 /* nearest kept position, the later one on a tie */
+                int ds = abs(pos[s] - j), db = abs(pos[best] - j);
+                if (ds < db || (ds == db && pos[s] > pos[best])) best = s;
+            }
+            widen(V, ((size_t)bh * N + j) * d, (size_t)d, dtype, row);
+            for (e = 0; e < d; ++e) sum[(size_t)best * d + e] += row[e];
+            cnt[best] += 1;
+        }
+        for (s = 0; s < m; ++s) {
+            for (e = 0; e < d; ++e) V_out[((size_t)bh * cap_rows + s) * d + e] = sum[(size_t)s * d + e] / (double)cnt[s];
+            if (count_opt) count_opt[(size_t)bh * cap_rows + s] = cnt[s];
+        }
+        if (count_opt) for (s = m; s < cap_rows; ++s) count_opt[(size_t)bh * cap_rows + s] = 0;
+        free(sum); free(cnt); free(row);
     }
     return 0;
 }

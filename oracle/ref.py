@@ -228,3 +228,27 @@ def evict(K, V, mass, dtype: str, budget: float, recent_ratio: float, cap_rows: 
     if rc:
         raise RuntimeError(f"kvm_ref_evict failed: {rc}")
     return kept, n_kept, K_out, V_out
+
+
+def evict_merge_values(K, V, mass, dtype: str, budget: float, recent_ratio: float, cap_rows: int, seq_lens=None):
+    """Comparison workload (value-only merging into the nearest kept token)
+    -> (kept, n_kept, K_out, V_out fp64, count (B, H, cap_rows))."""
+    lib = _load()
+    _check_storage(K, dtype)
+    _check_storage(V, dtype)
+    B, H, N, d = K.shape
+    mass = np.ascontiguousarray(mass, dtype=np.float64)
+    sl = _lens(seq_lens, B)
+    kept = np.empty((B, H, cap_rows), np.int32)
+    n_kept = np.empty((B, H), np.int32)
+    count = np.empty((B, H, cap_rows), np.int32)
+    K_out = np.zeros((B, H, cap_rows, d), np.float64)
+    V_out = np.zeros((B, H, cap_rows, d), np.float64)
+    lib.kvm_ref_evict_merge_values.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_double, ctypes.c_double,
+                                                                     ctypes.c_int] + [ctypes.c_void_p] * 8
+    rc = lib.kvm_ref_evict_merge_values(B, H, N, d, _DTYPE[dtype], _ptr(sl), float(budget), float(recent_ratio),
+                                        int(cap_rows), _ptr(K), _ptr(V), _ptr(mass), _ptr(kept), _ptr(n_kept),
+                                        _ptr(K_out), _ptr(V_out), _ptr(count))
+    if rc:
+        raise RuntimeError(f"kvm_ref_evict_merge_values failed: {rc}")
+    return kept, n_kept, K_out, V_out, count

@@ -243,3 +243,72 @@ def test_eviction_keeps_the_recent_window_and_the_largest_scores():
             assert np.array_equal(vo[0, h, :len(want)], V[0, h, want].astype(np.float64))
     kept, n_kept, _, _ = ref.evict(K, V, mass, "f32", 0.5, 0.17, 300, seq_lens=[37])
     assert n_kept[0, 0] == 18 and (kept[0, :, 18:] == -1).all() and kept[0, 0, 17] == 36
+
+
+# ---------------------------------------------------------------------------------------------
+# comparison workload: value-only merging into the nearest kept token (Section 2.3; a reading)
+# ---------------------------------------------------------------------------------------------
+
+def _values_by_hand(n, keep_positions, d=128):
+    """Scores that make the eviction policy keep exactly keep_positions (no recent window), values
+    whose first element is the token index and whose second is 1."""
+    K = np.zeros((1, 1, n, d), np.float32)
+    V = np.zeros((1, 1, n, d), np.float32)
+    V[0, 0, :, 0] = np.arange(n)
+    V[0, 0, :, 1] = 1.0
+    mass = np.zeros((1, 1, n))
+    mass[0, 0, list(keep_positions)] = 1.0
+    K[0, 0, :, 2] = np.arange(n)                             # a key tells its position
+    return K, V, mass
+
+
+def test_value_merge_worked_examples():
+    # kept 1 and 6 of 8 tokens: tokens 0..3 are nearest to 1 (token 3: distance 2 against 3), 4..7 to 6
+    K, V, mass = _values_by_hand(8, (1, 6))
+    kept, n_kept, ko, vo, cnt = ref.evict_merge_values(K, V, mass, "f32", 0.25, 0.0, 2)
+    assert n_kept[0, 0] == 2 and kept[0, 0].tolist() == [1, 6] and cnt[0, 0].tolist() == [4, 4]
+    assert vo[0, 0, :, 0].tolist() == [1.5, 5.5] and vo[0, 0, :, 1].tolist() == [1.0, 1.0]
+    assert ko[0, 0, :, 2].tolist() == [1.0, 6.0]             # keys: the kept rows, untouched
+    # kept 1 and 5: token 3 is as far from 1 as from 5 and goes to the later one
+    K, V, mass = _values_by_hand(8, (1, 5))
+    kept, n_kept, ko, vo, cnt = ref.evict_merge_values(K, V, mass, "f32", 0.25, 0.0, 2)
+    assert cnt[0, 0].tolist() == [3, 5]
+    assert vo[0, 0, :, 0].tolist() == [1.0, (3 + 4 + 5 + 6 + 7) / 5]
+    # a single kept token takes everything; tokens after the last kept one go to it
+    K, V, mass = _values_by_hand(9, (2,))
+    kept, n_kept, ko, vo, cnt = ref.evict_merge_values(K, V, mass, "f32", 0.12, 0.0, 1)
+    assert kept[0, 0].tolist() == [2] and cnt[0, 0].tolist() == [9] and vo[0, 0, 0, 0] == 4.0
+    # everything kept: the identity
+    K, V, mass = _values_by_hand(8, range(8))
+    kept, n_kept, ko, vo, cnt = ref.evict_merge_values(K, V, mass, "f32", 1.0, 0.0, 8)
+    assert np.array_equal(vo[0, 0], V[0, 0].astype(np.float64)) and (cnt == 1).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_value_merge_equals_means_over_midpoint_ranges(dtype):
+    """The nearest kept token by position is the same as cutting the sequence half-way between
+    neighbouring kept tokens (the token in the middle of an even gap goes to the later one): the
+    ranges are rebuilt with numpy from the kept positions and averaged."""
+    n, H = 700, 3
+    parts = [synth.gen_slice(9, h, n, 128, 1, None, dtype) for h in range(H)]
+    K = np.stack([p[1] for p in parts])[None]
+    V = np.stack([p[2] for p in parts])[None]
+    mass = np.random.default_rng(2).uniform(0, 1, (1, H, n))
+    # bf16 travels as its 16 bits; the upper half of an fp32 is the same number
+    Vf = (V.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if dtype == "bf16" else V.astype(np.float64)
+    for budget, recent, lens in ((0.5, 0.17, None), (0.1, 0.02, None), (0.35, 0.08, [413])):
+        cap = math.floor(budget * n)
+        kept, n_kept, ko, vo, cnt = ref.evict_merge_values(K, V, mass, dtype, budget, recent, cap, seq_lens=lens)
+        k2, n2, ko2, _ = ref.evict(K, V, mass, dtype, budget, recent, cap, seq_lens=lens)
+        assert np.array_equal(kept, k2) and np.array_equal(n_kept, n2) and np.array_equal(ko, ko2)
+        nn = n if lens is None else lens[0]
+        for h in range(H):
+            m = int(n_kept[0, h])
+            p = kept[0, h, :m].astype(np.int64)
+            edges = np.concatenate([[0], -((-(p[:-1] + p[1:])) // 2), [nn]])      # ceil of the midpoints
+            assert np.array_equal(cnt[0, h, :m], np.diff(edges))
+            for s in range(m):
+                want = Vf[0, h, edges[s]:edges[s + 1]].mean(axis=0)
+                np.testing.assert_allclose(vo[0, h, s], want, rtol=1e-12, atol=1e-13)
+            # nothing is lost: the means weighted by their counts add up to the sum of all values
+            np.testing.assert_allclose((vo[0, h, :m] * cnt[0, h, :m, None]).sum(0), Vf[0, h, :nn].sum(0), rtol=1e-10, atol=1e-10)
