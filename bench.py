@@ -77,8 +77,10 @@ def main() -> int:
                     help="merge weights (average = the average weighted merging of Section 4.2)")
     ap.add_argument("--pivot", choices=["max-score", "last", "random"], default="max-score",
                     help="pivot rule (last = largest index, Section 4.2; random = Section 5.4)")
-    ap.add_argument("--method", choices=["merge", "evict", "append"], default="merge",
+    ap.add_argument("--method", choices=["merge", "evict", "evict-merge-values", "append"], default="merge",
                     help="evict = the comparison workload: attention mass, then plain eviction by score (kvm_evict); "
+                         "evict-merge-values = the same with the evicted values averaged into the nearest kept token "
+                         "(kvm_evict_merge_values); "
                          "append = decode-time refresh: one more query row added to the scores (kvm_attn_mass_append), "
                          "then sets and merge again")
     ap.add_argument("--sets", choices=["adjacent", "anchor"], default="adjacent",
@@ -189,12 +191,15 @@ def main() -> int:
         else:
             kb.kvm_attn_mass_from_lse(shape, Qd, Kd, row_lse, buf.mass, buf.ws)
 
-    evict = args.method == "evict"
+    evict = args.method in ("evict", "evict-merge-values")
     if evict:
-        variant = "comparison workload: eviction by score" + ("; row statistics given by the caller" if row_lse is not None else "")
+        evict_call = kb.kvm_evict if args.method == "evict" else kb.kvm_evict_merge_values
+        variant = ("comparison workload: eviction by score" if args.method == "evict" else
+                   "comparison workload: eviction by score, evicted values averaged into the nearest kept token") + \
+            ("; row statistics given by the caller" if row_lse is not None else "")
         # kept positions go where the pivots would, their count where the set count would
         def rest():
-            kb.kvm_evict(shape, params, Kd, Vd, buf.mass, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.ws)
+            evict_call(shape, params, Kd, Vd, buf.mass, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.ws)
         buf.status.zero_()
     def identify():
         if append:
@@ -310,7 +315,7 @@ def main() -> int:
     # ---- the oracle on the host cores, on a sample of the same slices --------------------------
     cpu = None
     if args.cpu_slices > 0 and evict:
-        print("bench.py: no CPU baseline leg for --method evict (use --cpu-slices 0)", file=sys.stderr)
+        print("bench.py: no CPU baseline leg for the comparison workloads (use --cpu-slices 0)", file=sys.stderr)
     if args.cpu_slices > 0 and not evict:
         from oracle import ref
 

@@ -7,7 +7,8 @@
  *   kvm_attn_mass      aggregated attention score of every key
  *   kvm_identify_sets  contiguous merging sets + pivot of each set
  *   kvm_merge          Gaussian-kernel weighted merge into a compacted cache
- * (kvm_evict is a comparison workload: plain eviction by the same scores)
+ * (kvm_evict and kvm_evict_merge_values are comparison workloads: plain eviction by the same
+ *  scores, and eviction with the evicted values averaged into the kept ones)
  *
  * Conventions for every call
  *   - Every tensor pointer is a DEVICE pointer to contiguous memory, innermost
@@ -342,6 +343,20 @@ kvm_status kvm_merge_static(const kvm_shape *shape, const kvm_params *params, co
 kvm_status kvm_evict(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
                      const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out,
                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Second comparison workload, not part of the method: value-only merging.  Section 2.3 says of
+ * the value-merging scheme the paper compares with only that the value states about to be
+ * evicted are merged into the conserved ones; the reading built here: the selection is
+ * kvm_evict's; keys of evicted tokens are dropped; every evicted token's value goes to the kept
+ * token nearest to it by position (equal distances: the later one), and a kept token's new
+ * value is the plain mean of its own value and those that went to it (fp32 sums, one rounding
+ * to the cache type; a kept token that receives nothing keeps its bits).
+ * Arguments, layouts, workspace and errors exactly as for kvm_evict; V_out holds the means.
+ */
+kvm_status kvm_evict_merge_values(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                                  const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out,
+                                  void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Per-kernel timing for benchmarks (not part of the method; no citation).  While

@@ -25,7 +25,7 @@ KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
            "kvm_attn_mass_from_lse", "kvm_attn_mass_append", "kvm_sim_append",
-           "kvm_identify_sets", "kvm_merge", "kvm_merge_refresh", "kvm_merge_static", "kvm_evict", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
+           "kvm_identify_sets", "kvm_merge", "kvm_merge_refresh", "kvm_merge_static", "kvm_evict", "kvm_evict_merge_values", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
 _TORCH_DTYPE = {torch.float32: KVM_F32, torch.float16: KVM_F16, torch.bfloat16: KVM_BF16}
@@ -90,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_merge_static.restype = ctypes.c_int
     lib.kvm_evict.argtypes = [ctypes.POINTER(KvmShape), ctypes.POINTER(KvmParams)] + [P] * 8 + [S, P]
     lib.kvm_evict.restype = ctypes.c_int
+    lib.kvm_evict_merge_values.argtypes = lib.kvm_evict.argtypes
+    lib.kvm_evict_merge_values.restype = ctypes.c_int
     lib.kvm_profile_enable.argtypes = [ctypes.c_int32]
     lib.kvm_profile_enable.restype = ctypes.c_int
     lib.kvm_profile_collect.argtypes = [ctypes.POINTER(KvmKernelTime), ctypes.c_int32]
@@ -297,8 +299,7 @@ def kvm_merge_static(shape: KvmShape, params: KvmParams, K, V, set_start, pivot,
         _ptr(K_out), _ptr(V_out), _ptr(w_opt), _stream()))
 
 
-def kvm_evict(shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_out, V_out, ws):
-    """Comparison workload: keep the recent window and the largest scores, gather their rows."""
+def _evict(fn: str, shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_out, V_out, ws):
     _same_device(K, V, mass, kept, n_kept, K_out, V_out, ws)
     B, H, N, d = shape.B, shape.H_kv, shape.N, shape.d
     cap = kvm_out_capacity(shape, params)
@@ -311,9 +312,19 @@ def kvm_evict(shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_ou
         raise ValueError("kept and n_kept must be int32, mass float32")
     if not (K.dtype == V.dtype == K_out.dtype == V_out.dtype) or _TORCH_DTYPE[K.dtype] != shape.dtype:
         raise ValueError("dtype mismatch")
-    _check("kvm_evict", load_library().kvm_evict(
+    _check(fn, getattr(load_library(), fn)(
         ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), _ptr(mass), _ptr(kept), _ptr(n_kept), _ptr(K_out),
         _ptr(V_out), None if ws is None else _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_evict(shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_out, V_out, ws):
+    """Comparison workload: keep the recent window and the largest scores, gather their rows."""
+    _evict("kvm_evict", shape, params, K, V, mass, kept, n_kept, K_out, V_out, ws)
+
+
+def kvm_evict_merge_values(shape: KvmShape, params: KvmParams, K, V, mass, kept, n_kept, K_out, V_out, ws):
+    """Comparison workload: as kvm_evict, the evicted values averaged into the nearest kept token's value."""
+    _evict("kvm_evict_merge_values", shape, params, K, V, mass, kept, n_kept, K_out, V_out, ws)
 
 
 def kvm_profile_enable(max_launches: int):

@@ -973,9 +973,132 @@ static void launch_gather(const kvm_shape &sh, int cap_rows, const void *K, cons
                        (T *)V_out, kept, n_kept, sh.N, cap_rows, tiles);
 }
 
+// Second comparison workload (value-only merging): K_out[s] = K[kept[s]]; V_out[s] = mean of the
+// values of the tokens that are nearest to kept[s] among the kept positions (equal distances: the
+// later one), i.e. of the range that ends half-way to either neighbour.  One 16-lane group per kept
+// row for the first 32 rows of its range (4 loads in flight); what a longer range has left is summed
+// by the whole workgroup, one range after the other (64 rows in flight, partial sums through LDS in
+// a fixed order): scores that fall with the position leave one gap of thousands of tokens between
+// the heavy tokens and the recent window, and half of all values sit in it.
+// fp32 sums, one division, one rounding.
+constexpr int VM_OWN_ROWS = 32;
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_merge_values_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                                   T *__restrict__ K_out, T *__restrict__ V_out,
+                                                                   const int32_t *__restrict__ kept,
+                                                                   const int32_t *__restrict__ n_kept,
+                                                                   const int32_t *__restrict__ seq_lens, int H, int N,
+                                                                   int cap_rows, int tiles_per_slice)
+{
+    using E = Elem<T>;
+    using Raw = typename E::Raw;
+    __shared__ int rest_lo[16], rest_hi[16];
+    __shared__ float red[4][16][9];                          // per wave and 8-element chunk (padded)
+    const int slice = blockIdx.x / tiles_per_slice;
+    // Consecutive workgroups go to consecutive XCDs, and the long ranges sit at the same tiles in
+    // every slice: the tiles are rotated by the slice index so that they do not all meet on the
+    // same one or two XCDs.
+    const int tile = (blockIdx.x - slice * tiles_per_slice + slice) % tiles_per_slice;
+    const int c = threadIdx.x & 15, group = threadIdx.x >> 4, wave = threadIdx.x >> 6;
+    const int n = clamp_len(seq_lens, slice / H, N);
+    const int m = min(max(n_kept[slice], 0), cap_rows);
+    if (tile * 16 >= m) return;                              // (the whole workgroup)
+    const int s = tile * 16 + group;
+    const int32_t *kp = kept + (size_t)slice * cap_rows;
+    const T *Ks = K + (size_t)slice * N * HEAD_DIM;
+    const T *Vs = V + (size_t)slice * N * HEAD_DIM;
+    // the range of this group's kept token (positions are clamped into the slice: the list may
+    // hold anything when the caller's buffers are inconsistent)
+    int lo = 0, hi = 0, p = 0;
+    if (s < m) {
+        p = min(max(kp[s], 0), n - 1);
+        lo = s == 0 ? 0 : (min(max(kp[s - 1], 0), n - 1) + p + 1) >> 1;
+        hi = s == m - 1 ? n : (p + min(max(kp[s + 1], 0), n - 1) + 1) >> 1;
+        lo = min(lo, p);
+        hi = max(hi, p + 1);
+    }
+    const int cnt = hi - lo;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    Raw kr;
+    if (s < m) kr = E::load(Ks + (size_t)p * HEAD_DIM, c);
+    // the group's own part
+    const int own_hi = min(hi, lo + VM_OWN_ROWS);
+    if (c == 0) { rest_lo[group] = own_hi; rest_hi[group] = hi; }
+    for (int j0 = lo; j0 < own_hi; j0 += 4) {
+        Raw r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (j0 + u < own_hi) r[u] = E::load(Vs + (size_t)(j0 + u) * HEAD_DIM, c);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (j0 + u < own_hi) {
+                float x[8];
+                E::to_float(r[u], x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += x[e];
+            }
+    }
+    __syncthreads();
+    // what longer ranges have left, by the whole workgroup
+    for (int g = 0; g < 16; ++g) {
+        const int r_lo = rest_lo[g], r_hi = rest_hi[g];
+        if (r_hi <= r_lo) continue;                          // (the same for the whole workgroup)
+        float part[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[e] = 0.f;
+        for (int j0 = r_lo; j0 < r_hi; j0 += 64) {
+            Raw r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j0 + 16 * u + group < r_hi) r[u] = E::load(Vs + (size_t)(j0 + 16 * u + group) * HEAD_DIM, c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j0 + 16 * u + group < r_hi) {
+                    float x[8];
+                    E::to_float(r[u], x);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) part[e] += x[e];
+                }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[e] = rows4_sum(part[e]);
+        if ((threadIdx.x & 48) == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[wave][c][e] = part[e];
+        }
+        __syncthreads();
+        if (group == g) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (red[0][c][e] + red[1][c][e]) + (red[2][c][e] + red[3][c][e]);
+        }
+        __syncthreads();                                     // red is written again for the next long range
+    }
+    if (s < m) {
+        const float cf = (float)cnt;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] / cf;
+        E::store(K_out + ((size_t)slice * cap_rows + s) * HEAD_DIM, c, kr);
+        E::store(V_out + ((size_t)slice * cap_rows + s) * HEAD_DIM, c, E::from_float(acc));   // a lone value comes back bit for bit
+    }
+}
+
+template <typename T>
+static void launch_gather_merge_values(const kvm_shape &sh, int cap_rows, const void *K, const void *V, void *K_out,
+                                       void *V_out, const int32_t *kept, const int32_t *n_kept, hipStream_t st)
+{
+    const int tiles = (cap_rows + 15) / 16;
+    const long long blocks = (long long)sh.B * sh.H_kv * tiles;
+    ProfScope prof("gather_merge_values_kernel", st);
+    hipLaunchKernelGGL(gather_merge_values_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, (const T *)K, (const T *)V,
+                       (T *)K_out, (T *)V_out, kept, n_kept, sh.seq_lens, sh.H_kv, sh.N, cap_rows, tiles);
+}
+
 kvm_status launch_evict(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, uint8_t *flags,
-                        hipStream_t st)
+                        bool merge_values, hipStream_t st)
 {
     const long long slices = (long long)sh.B * sh.H_kv;
     if (slices == 0) return KVM_OK;
@@ -996,6 +1119,14 @@ kvm_status launch_evict(const kvm_shape &sh, const kvm_params &pr, int cap_rows,
     }
     kvm_status rc = check_launch("evict_select_kernel");
     if (rc != KVM_OK || cap_rows == 0 || sh.N == 0) return rc;
+    if (merge_values) {
+        switch (sh.dtype) {
+        case KVM_F32: launch_gather_merge_values<float>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
+        case KVM_F16: launch_gather_merge_values<half_t>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
+        default: launch_gather_merge_values<bf16_t>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
+        }
+        return check_launch("gather_merge_values_kernel");
+    }
     switch (sh.dtype) {
     case KVM_F32: launch_gather<float>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;
     case KVM_F16: launch_gather<half_t>(sh, cap_rows, K, V, K_out, V_out, kept, n_kept, st); break;

@@ -270,26 +270,41 @@ kvm_status kvm_identify_sets(const kvm_shape *shape, const kvm_params *params, c
                            inv_norm, run, flags, slice_status, (hipStream_t)stream);
 }
 
-kvm_status kvm_evict(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V, const float *mass,
-                     int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, void *ws, size_t ws_bytes, void *stream)
+static kvm_status evict_common(const char *fn, bool merge_values, const kvm_shape *shape, const kvm_params *params, const void *K,
+                               const void *V, const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out,
+                               void *ws, size_t ws_bytes, void *stream)
 {
-    kvm_status rc = check_shape(shape, "kvm_evict");
+    kvm_status rc = check_shape(shape, fn);
     if (rc != KVM_OK) return rc;
-    rc = check_params(params, "kvm_evict");
+    rc = check_params(params, fn);
     if (rc != KVM_OK) return rc;
     if (shape->B == 0) return KVM_OK;
     const int cap = capacity(shape, params);
     if (!n_kept || (cap > 0 && (!kept || !K_out || !V_out)) || (shape->N > 0 && (!K || !V || !mass))) {
-        set_error("kvm_evict: a required pointer is NULL");
+        set_error("%s: a required pointer is NULL", fn);
         return KVM_ERR_INVALID_ARG;
     }
     if (ws_identify(shape) > 0 && (!ws || ws_bytes < ws_identify(shape))) {
-        set_error("kvm_evict: workspace of %zu bytes needed, %zu given", ws_identify(shape), ws ? ws_bytes : (size_t)0);
+        set_error("%s: workspace of %zu bytes needed, %zu given", fn, ws_identify(shape), ws ? ws_bytes : (size_t)0);
         return KVM_ERR_WORKSPACE;
     }
     const size_t tok = (size_t)shape->B * shape->H_kv * shape->N;
     uint8_t *flags = (uint8_t *)ws + 3 * align_up(tok * sizeof(float), 256);
-    return launch_evict(*shape, *params, cap, K, V, mass, kept, n_kept, K_out, V_out, flags, (hipStream_t)stream);
+    return launch_evict(*shape, *params, cap, K, V, mass, kept, n_kept, K_out, V_out, flags, merge_values, (hipStream_t)stream);
+}
+
+kvm_status kvm_evict(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V, const float *mass,
+                     int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, void *ws, size_t ws_bytes, void *stream)
+{
+    return evict_common("kvm_evict", false, shape, params, K, V, mass, kept, n_kept, K_out, V_out, ws, ws_bytes, stream);
+}
+
+kvm_status kvm_evict_merge_values(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,
+                                  const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, void *ws,
+                                  size_t ws_bytes, void *stream)
+{
+    return evict_common("kvm_evict_merge_values", true, shape, params, K, V, mass, kept, n_kept, K_out, V_out, ws, ws_bytes,
+                        stream);
 }
 
 kvm_status kvm_merge(const kvm_shape *shape, const kvm_params *params, const void *K, const void *V,

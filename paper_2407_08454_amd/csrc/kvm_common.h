@@ -198,7 +198,7 @@ kvm_status launch_merge_static(const kvm_shape &sh, const kvm_params &pr, int ca
                                void *V_out, float *w_opt, hipStream_t st);
 kvm_status launch_evict(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,
                         const float *mass, int32_t *kept, int32_t *n_kept, void *K_out, void *V_out, uint8_t *flags,
-                        hipStream_t st);
+                        bool merge_values, hipStream_t st);
 size_t merge_workspace_bytes(const kvm_shape &sh);
 size_t merge_refresh_workspace_bytes(const kvm_shape &sh, int cap_rows);
 kvm_status launch_merge_refresh(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const void *V,

@@ -171,6 +171,15 @@ def test_host_detectable_errors_return_before_any_launch():
     assert refresh(_shape(), p, nbytes=4) == kb.KVM_ERR_WORKSPACE
     assert refresh(_shape(N=0), p, K=None) == kb.KVM_OK                           # nothing to do
 
+    for fn in (lib.kvm_evict, lib.kvm_evict_merge_values):                        # the two comparison workloads
+        def evict(sh, pr, K=one, ws=one, nbytes=1 << 30):
+            return fn(ctypes.byref(sh), ctypes.byref(pr), K, one, one, one, one, one, one, ws, nbytes, None)
+        assert evict(_shape(), p, K=None) == kb.KVM_ERR_INVALID_ARG
+        assert evict(_shape(d=256), p) == kb.KVM_ERR_UNSUPPORTED
+        assert evict(_shape(), p, ws=None) == kb.KVM_ERR_WORKSPACE
+        assert evict(_shape(), p, nbytes=8) == kb.KVM_ERR_WORKSPACE
+        assert evict(_shape(B=0), p, K=None) == kb.KVM_OK
+
 
 def test_binding_refuses_mismatched_tensors_on_the_host():
     import torch

@@ -1118,6 +1118,53 @@ def test_evict_matches_the_oracle(dtype):
                 assert (gk[b, h, m:] == 0).all()              # rows beyond the kept ones are not written
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_evict_merge_values_matches_the_oracle(dtype):
+    """Value-only merging (comparison workload): kept positions and keys bit-exact, the averaged values
+    to the bar of the merged rows.  Scores fall with the position in slice (0, 1), so the kept tokens
+    crowd at both ends and one of them averages hundreds of values (the part a whole wave sums)."""
+    n = 2100
+    lens = [n, 1000, 0, 1, 77]
+    _say(f"evict + value merge: {dtype}, lens {lens}")
+    Q, K, V = _slices(36, 5, 2, lens, n, 128, 1, dtype)
+    rng = np.random.default_rng(10)
+    mass = (rng.random((5, 2, n)) + 0.01).astype(np.float32)
+    mass[0, 1] = (3.0 - np.arange(n) / n + 0.001 * rng.random(n)).astype(np.float32)
+    mass[0, 0, 300:700] = mass[0, 0, 300]
+    for budget, recent in ((0.5, 0.17), (0.35, 0.08), (0.05, 0.01), (0.3, 0.3), (1.0, 0.0)):
+        params = kb.make_params(budget, recent, 0.0)
+        Kd, Vd = gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+        sh = kb.make_shape(Kd, 1, gu.lens_dev(lens))
+        cap = kb.kvm_out_capacity(sh, params)
+        kept = torch.full((5, 2, cap), -7, dtype=torch.int32, device="cuda")
+        n_kept = torch.full((5, 2), -7, dtype=torch.int32, device="cuda")
+        Ko = torch.zeros((5, 2, cap, 128), dtype=gu.TORCH_DT[dtype], device="cuda")
+        Vo = torch.zeros_like(Ko)
+        ws = torch.empty(kb.kvm_workspace_bytes(sh, params), dtype=torch.uint8, device="cuda")
+        kb.kvm_evict_merge_values(sh, params, Kd, Vd, torch.from_numpy(mass).cuda(), kept, n_kept, Ko, Vo, ws)
+        torch.cuda.synchronize()
+        ok, on, oko, ovo, cnt = ref.evict_merge_values(K, V, mass.astype(np.float64), dtype, budget, recent, cap, lens)
+        assert np.array_equal(n_kept.cpu().numpy(), on) and np.array_equal(kept.cpu().numpy(), ok)
+        gk, gv = gu.to_host_f64(Ko), gu.to_host_f64(Vo)
+        worst, longest = 0.0, 0
+        for b in range(5):
+            for h in range(2):
+                m = int(on[b, h])
+                assert np.array_equal(gk[b, h, :m], oko[b, h, :m])
+                assert (gk[b, h, m:] == 0).all() and (gv[b, h, m:] == 0).all()    # rows beyond the kept ones are not written
+                if m == 0:
+                    continue
+                lone = cnt[b, h, :m] == 1
+                assert np.array_equal(gv[b, h, :m][lone], ovo[b, h, :m][lone])    # nothing received: the same bits
+                err = gu.row_rel_err(gv[b, h, :m], ovo[b, h, :m]).max()
+                assert err <= gu.kv_tol(dtype), f"slice ({b},{h}) budget {budget}: value error {err:.3e}"
+                assert gu.ulp_excess(gv[b, h, :m], ovo[b, h, :m], dtype).max() <= 2e-5
+                worst, longest = max(worst, float(err)), max(longest, int(cnt[b, h, :m].max()))
+        _say(f"  budget {budget}: worst value error {worst:.2e}, longest mean over {longest} values")
+        if budget == 0.05:
+            assert longest > 64                               # the cooperative part ran
+
+
 # ---------------------------------------------------------------------------------------------
 # streams and graphs: the calls only enqueue work on the caller's stream
 # ---------------------------------------------------------------------------------------------
