@@ -359,7 +359,7 @@ def main() -> int:
         cpu["single_core"] = {"value": rate1, "unit": "token-slices/s", "cores": 1,
                               "sample": f"{S1} of {B * H} slices, {what} in fp64, {secs1:.1f} s wall on one thread"}
 
-    metric, work = METRIC, token_slices
+    metric, work = (METRIC if args.config == 2 else METRIC.split(" at ")[0]), token_slices
     refresh = None
     if append:                                              # one token per slice and step
         metric, work = "decode-time refresh: appended tokens/sec (all layers x heads) at Llama2-7B N=4096", B * H

@@ -531,7 +531,7 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, co
     {
         const int wgs = tiles >= 8 ? (tiles + 1) / 2 : tiles;   // as for the row statistics
         const long long blocks = (long long)((n_kv + 7) / 8) * 8 * wgs;
-        ProfScope prof("attn_colsum_kernel", st);
+        ProfScope prof(pipe ? "attn_colsum_pipe_kernel" : "attn_colsum_kernel", st);
         if (pipe) launch_colsum_pipe(sh, Q, K, lse, mass, n_pad, c, st);
         else hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
                            (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, wgs, c);

@@ -1239,8 +1239,9 @@ kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_ro
             walk_lds_bytes = (size_t)sh.N * 3;
         }
     }
-    ProfScope prof("segment_kernel", st);
-    if (!anchor && sh.N > 0 && sh.N <= 1024 * SR_ITEMS) {
+    const bool in_registers = !anchor && sh.N > 0 && sh.N <= 1024 * SR_ITEMS;
+    ProfScope prof(in_registers ? "segment_reg_kernel" : "segment_kernel", st);
+    if (in_registers) {
         // 16 tokens per thread in registers: as many threads as the slice needs
         if (sh.N <= 256 * SR_ITEMS) hipLaunchKernelGGL(segment_reg_kernel<256>, dim3((unsigned)slices), dim3(256), 0, st, a);
         else if (sh.N <= 512 * SR_ITEMS) hipLaunchKernelGGL(segment_reg_kernel<512>, dim3((unsigned)slices), dim3(512), 0, st, a);
