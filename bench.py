@@ -72,6 +72,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None, help="generate only this many layers (not the headline run)")
     ap.add_argument("--budget", type=float, default=0.5)
     ap.add_argument("--cpu-slices", type=int, default=512, help="slices the oracle is timed on (0 = skip)")
+    ap.add_argument("--sim-from-score-pass", action="store_true",
+                    help="similarities written by the score pass (kvm_attn_mass_sim) instead of kvm_identify_sets' own scan of K")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events inside the timed region")
     ap.add_argument("--weights", choices=["gaussian", "average"], default="gaussian",
                     help="merge weights (average = the average weighted merging of Section 4.2)")
@@ -139,7 +141,7 @@ def main() -> int:
     variant = (f"sets {args.sets}, weights {args.weights}, pivot {args.pivot}, "
                f"sigma {'per set' if args.sigma is None else args.sigma}")
     shape = kb.make_shape(Kd, G, sl)
-    buf = kb.Buffers(shape, params, "cuda", tdt)
+    buf = kb.Buffers(shape, params, "cuda", tdt, with_sim=args.sim_from_score_pass)
 
     row_lse = sim_carried = None
     if args.row_stats == "given":
@@ -179,6 +181,16 @@ def main() -> int:
         # the appended tokens' query rows, one contiguous (B, H G, d) block per step
         q_steps = Qd[:, :, N - grow:N].permute(2, 0, 1, 3).contiguous()
 
+    # on request the similarities come out of the score pass (kvm_attn_mass_sim) and the sets' own scan of K is skipped
+    fused = (args.sim_from_score_pass and args.sets == "adjacent" and row_lse is None and not append
+             and args.method == "merge")
+    params_sets = params
+    if fused:
+        variant += "; adjacent similarities written by the score pass"
+        sim_carried = buf.sim
+        params_sets = kb.KvmParams.from_buffer_copy(params)
+        params_sets.sim_given = 1
+
     def attn_mass():
         if append:
             sl.add_(1)                                          # the token's key and value are already in K, V
@@ -186,6 +198,8 @@ def main() -> int:
             q_new = q_steps[n_now[0] - 1 - (N - grow)]
             kb.kvm_attn_mass_append(shape, q_new, Kd, buf.mass, buf.ws)
             kb.kvm_sim_append(shape, Kd, sim_carried)
+        elif fused:
+            kb.kvm_attn_mass_sim(shape, Qd, Kd, buf.mass, sim_carried, buf.ws)
         elif row_lse is None:
             kb.kvm_attn_mass(shape, Qd, Kd, buf.mass, buf.ws)
         else:
@@ -206,8 +220,8 @@ def main() -> int:
             new = maps[1 - cur[0]]
             kb.kvm_identify_sets(shape, params, Kd, buf.mass, *new, sim_carried, buf.status, buf.ws)
         else:
-            kb.kvm_identify_sets(shape, params, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, sim_carried,
-                                 buf.status, buf.ws)
+            kb.kvm_identify_sets(shape, params_sets, Kd, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets,
+                                 sim_carried, buf.status, buf.ws)
 
     def merge():
         if append:
@@ -272,7 +286,7 @@ def main() -> int:
     if args.keys == "identical":
         variant += "; identical keys (one merging set per slice)"
     headline = (args.keys == "ar1" and args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
-                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None)
+                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None and not fused)
 
     counters = measured_traffic("llama2-7b_n4096_f16") if headline else {}
 
@@ -305,7 +319,8 @@ def main() -> int:
     # (K twice, V once, merged rows, scores, similarities and maps: 3 n d s + 2 M d s + 20 n per slice)
     stage_fractions = None
     if not append and not evict and stage_ms[0] > 0:
-        bytes_bc = float(3 * token_slices * d * esz + 2 * M_total * d * esz + 20 * token_slices)
+        # (with the similarities written by the score pass, stage (b) no longer reads K: 2 n d s instead of 3)
+        bytes_bc = float((2 if fused else 3) * token_slices * d * esz + 2 * M_total * d * esz + 20 * token_slices)
         stage_fractions = {
             "attn_mass_of_mfma_peak": flops_attn / (stage_ms[0] / args.steps * 1e-3) / PEAK_MFMA[dtype],
             "identify_plus_merge_of_hbm_peak": bytes_bc / ((stage_ms[1] + stage_ms[2]) / args.steps * 1e-3) / PEAK_HBM,

@@ -158,6 +158,21 @@ kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, f
                          void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * kvm_attn_mass and, in the same pass over K, the cosine similarities of adjacent key states
+ * (Section 3.1 Eq. (2); the input of Algorithm 1): the kernel that takes the column sums of
+ * Eq. (7) holds every key in registers anyway, so the scan of K that kvm_identify_sets starts
+ * with is not needed afterwards.
+ *   sim   out  (B, H_kv, N) float32: sim[j] = cos(k_{j-1}, k_j); 0 for j = 0, for a key of zero
+ *              norm and at positions >= n_b -- what kvm_identify_sets returns in sim_opt, up to
+ *              the order of the fp32 additions (a few 1e-7)
+ * Pass sim to kvm_identify_sets as sim_opt with params.sim_given = 1 (adjacent rule).  Other
+ * arguments, workspace, result and errors as for kvm_attn_mass; mass is bit for bit the same.
+ * (fp32 caches: the similarities come from the same streaming scan kvm_identify_sets uses.)
+ */
+kvm_status kvm_attn_mass_sim(const kvm_shape *shape, const void *Q, const void *K, float *mass, float *sim,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
  * The same map for a caller that already holds the softmax row statistics of
  * Eq. (1), as prefill attention kernels keep them: only the column sums of
  * Eq. (7) remain, about half of kvm_attn_mass's work.

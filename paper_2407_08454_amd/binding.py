@@ -25,7 +25,7 @@ KVM_SETS_ADJACENT, KVM_SETS_ANCHOR = 0, 1
 
 EXPORTS = ("kvm_params_for_budget", "kvm_out_capacity", "kvm_workspace_bytes", "kvm_attn_mass",
            "kvm_attn_mass_from_lse", "kvm_attn_mass_append", "kvm_sim_append",
-           "kvm_identify_sets", "kvm_merge", "kvm_merge_refresh", "kvm_merge_static", "kvm_evict", "kvm_evict_merge_values", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
+           "kvm_attn_mass_sim", "kvm_identify_sets", "kvm_merge", "kvm_merge_refresh", "kvm_merge_static", "kvm_evict", "kvm_evict_merge_values", "kvm_profile_enable", "kvm_profile_collect", "kvm_profile_disable",
            "kvm_last_error", "kvm_version")
 
 _TORCH_DTYPE = {torch.float32: KVM_F32, torch.float16: KVM_F16, torch.bfloat16: KVM_BF16}
@@ -74,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.kvm_workspace_bytes.restype = S
     lib.kvm_attn_mass.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, S, P]
     lib.kvm_attn_mass.restype = ctypes.c_int
+    lib.kvm_attn_mass_sim.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, P, S, P]
+    lib.kvm_attn_mass_sim.restype = ctypes.c_int
     lib.kvm_attn_mass_from_lse.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, P, S, P]
     lib.kvm_attn_mass_from_lse.restype = ctypes.c_int
     lib.kvm_attn_mass_append.argtypes = [ctypes.POINTER(KvmShape), P, P, P, P, S, P]
@@ -183,6 +185,16 @@ def kvm_attn_mass(shape: KvmShape, Q, K, mass, ws):
     _check_attn_operands(shape, Q, K, mass)
     _check("kvm_attn_mass", load_library().kvm_attn_mass(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(mass), _ptr(ws),
                                                          ws.numel() * ws.element_size(), _stream()))
+
+
+def kvm_attn_mass_sim(shape: KvmShape, Q, K, mass, sim, ws):
+    """kvm_attn_mass, and sim (B, H_kv, N) float32 <- cosine similarity of every key to the one before it."""
+    _same_device(Q, K, mass, sim, ws)
+    _check_attn_operands(shape, Q, K, mass)
+    if sim.dtype != torch.float32 or tuple(sim.shape) != (shape.B, shape.H_kv, shape.N):
+        raise ValueError("sim must be float32 of shape (B, H_kv, N)")
+    _check("kvm_attn_mass_sim", load_library().kvm_attn_mass_sim(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(mass), _ptr(sim),
+                                                                 _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def kvm_attn_mass_from_lse(shape: KvmShape, Q, K, row_lse, mass, ws):
@@ -345,7 +357,7 @@ def kvm_profile_disable():
 class Buffers:
     """Caller-owned device buffers for one shape/params pair (allocated once with torch)."""
 
-    def __init__(self, shape: KvmShape, params: KvmParams, device, dtype, with_debug: bool = False):
+    def __init__(self, shape: KvmShape, params: KvmParams, device, dtype, with_debug: bool = False, with_sim: bool = False):
         B, H, N, d = shape.B, shape.H_kv, shape.N, shape.d
         cap = kvm_out_capacity(shape, params)
         i32 = dict(dtype=torch.int32, device=device)
@@ -358,14 +370,25 @@ class Buffers:
         self.status = torch.empty((B, H), **i32)
         self.K_out = torch.empty((B, H, cap, d), dtype=dtype, device=device)
         self.V_out = torch.empty((B, H, cap, d), dtype=dtype, device=device)
-        self.sim = torch.empty((B, H, N), dtype=torch.float32, device=device) if with_debug else None
+        self.sim = torch.empty((B, H, N), dtype=torch.float32, device=device) if with_debug or with_sim else None
         self.w = torch.empty((B, H, N), dtype=torch.float32, device=device) if with_debug else None
         self.ws = torch.empty(max(kvm_workspace_bytes(shape, params), 256), dtype=torch.uint8, device=device)
 
 
-def compress(shape: KvmShape, params: KvmParams, Q, K, V, buf: Buffers):
-    """One pass of the whole hot path: three library calls on the current stream."""
-    kvm_attn_mass(shape, Q, K, buf.mass, buf.ws)
-    kvm_identify_sets(shape, params, K, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, buf.sim,
-                      buf.status, buf.ws)
+def compress(shape: KvmShape, params: KvmParams, Q, K, V, buf: Buffers, sim_from_score_pass: bool = False):
+    """One pass of the whole hot path: three library calls on the current stream.
+    sim_from_score_pass (adjacent rule only): the similarities come out of the score pass
+    (kvm_attn_mass_sim) and kvm_identify_sets skips its scan of K."""
+    if sim_from_score_pass and params.set_rule == KVM_SETS_ADJACENT and not params.sim_given:
+        if buf.sim is None:
+            raise ValueError("sim_from_score_pass needs Buffers(..., with_sim=True)")
+        kvm_attn_mass_sim(shape, Q, K, buf.mass, buf.sim, buf.ws)
+        given = KvmParams.from_buffer_copy(params)
+        given.sim_given = 1
+        kvm_identify_sets(shape, given, K, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, buf.sim,
+                          buf.status, buf.ws)
+    else:
+        kvm_attn_mass(shape, Q, K, buf.mass, buf.ws)
+        kvm_identify_sets(shape, params, K, buf.mass, buf.set_id, buf.set_start, buf.pivot, buf.n_sets, buf.sim,
+                          buf.status, buf.ws)
     kvm_merge(shape, params, K, V, buf.set_start, buf.pivot, buf.n_sets, buf.K_out, buf.V_out, buf.w, buf.ws)

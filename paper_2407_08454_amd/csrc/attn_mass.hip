@@ -300,6 +300,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_lse_kernel(con
 template <typename T>
 __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const float *__restrict__ lse, float *__restrict__ mass,
+                                                                    float *__restrict__ sim_opt,
                                                                     const int32_t *__restrict__ seq_lens, int n_kvslices,
                                                                     int H, int G, int N, int n_pad, int tiles_per_slice,
                                                                     int wgs_per_slice, float c)
@@ -320,6 +321,7 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // scalar: per-wave branches stay scalar
     float *mass_s = mass + (size_t)kvslice * N;
+    float *sim_s = sim_opt ? sim_opt + (size_t)kvslice * N : nullptr;
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
     const typename TL::Offsets off = TL::offsets(wave, lane);
     const FragSlots fs = frag_slots<T>(lane);
@@ -332,7 +334,10 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     const int k_begin = tile * KEYS_PER_BLOCK;
     const int k0 = k_begin + wave * 32 * NB;
     if (k_begin >= n) {                                       // padding only: defined zeros
-        for (int j = k_begin + threadIdx.x; j < min(k_begin + KEYS_PER_BLOCK, N); j += ATT_BLOCK) mass_s[j] = 0.f;
+        for (int j = k_begin + threadIdx.x; j < min(k_begin + KEYS_PER_BLOCK, N); j += ATT_BLOCK) {
+            mass_s[j] = 0.f;
+            if (sim_s) sim_s[j] = 0.f;
+        }
         continue;
     }
 
@@ -359,6 +364,15 @@ __global__ __launch_bounds__(ATT_BLOCK, ATT_MIN_BLOCKS) void attn_colsum_kernel(
     u32x4 kf[NB][M::FRAGS];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) load_stationary<T>(Ks, k0 + 32 * kb, n, lane, kf[kb]);
+    if constexpr (sizeof(T) == 2) {
+        if (sim_s) {                                          // the keys are here anyway: their adjacent similarities
+            u32x4 before[NB];
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) before[kb] = load_predecessor<T>(Ks, k0 + 32 * kb, n, lane);
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) stationary_cosine<T>(k0 + 32 * kb, n, N, lane, kf[kb], before[kb], sim_s);
+        }
+    }
 
     float part[NB][2];
 #pragma unroll
@@ -472,8 +486,8 @@ __global__ void __launch_bounds__(256) lse_import_kernel(const float *__restrict
     lse[(size_t)qslice * n_pad + q] = q < n ? row_lse[(size_t)qslice * N + q] * scale : pad;
 }
 
-void launch_colsum_pipe(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass, int n_pad, float c,
-                        hipStream_t st);
+void launch_colsum_pipe(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass, float *sim_opt,
+                        int n_pad, float c, hipStream_t st);
 
 // From this length on the column sums of 16-bit inputs are taken by attn_colsum_pipe_kernel
 // (attn_pipe.hip): measured 5 % faster at N = 16384, 1-3 % slower at N = 4096, where the eight
@@ -482,7 +496,7 @@ constexpr int COLSUM_PIPE_MIN_N = 8192;
 
 template <typename T>
 static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass, float *lse,
-                           hipStream_t st)
+                           float *sim_opt, hipStream_t st)
 {
     constexpr int ROWS = ATT_WAVES * 32 * Mma<T>::NBLK;
     const int tiles = (sh.N + ROWS - 1) / ROWS;
@@ -532,9 +546,10 @@ static kvm_status launch_t(const kvm_shape &sh, const void *Q, const void *K, co
         const int wgs = tiles >= 8 ? (tiles + 1) / 2 : tiles;   // as for the row statistics
         const long long blocks = (long long)((n_kv + 7) / 8) * 8 * wgs;
         ProfScope prof(pipe ? "attn_colsum_pipe_kernel" : "attn_colsum_kernel", st);
-        if (pipe) launch_colsum_pipe(sh, Q, K, lse, mass, n_pad, c, st);
+        if (pipe) launch_colsum_pipe(sh, Q, K, lse, mass, sim_opt, n_pad, c, st);
         else hipLaunchKernelGGL(attn_colsum_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q,
-                           (const T *)K, (const float *)lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, wgs, c);
+                           (const T *)K, (const float *)lse, mass, sizeof(T) == 2 ? sim_opt : nullptr, sh.seq_lens, n_kv, sh.H_kv,
+                           sh.G, sh.N, n_pad, tiles, wgs, c);
         return check_launch("attn_colsum_kernel");
     }
 }
@@ -546,14 +561,19 @@ int attn_row_tiles(int N) { return (N + 255) / 256; }
 
 // row_lse == nullptr: the row statistics are computed here (first score pass); otherwise the
 // caller's are imported and only the column-sum pass runs.
+// sim_opt != nullptr: the column-sum kernels also write the adjacent-key similarities (16-bit types;
+// fp32 keys sit in another register layout and get the streaming scan instead).
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass, float *lse,
-                            hipStream_t st)
+                            float *sim_opt, hipStream_t st)
 {
     if ((long long)sh.B * sh.H_kv == 0 || sh.N == 0) return KVM_OK;
     switch (sh.dtype) {
-    case KVM_F32: return launch_t<float>(sh, Q, K, row_lse, mass, lse, st);
-    case KVM_F16: return launch_t<half_t>(sh, Q, K, row_lse, mass, lse, st);
-    default: return launch_t<bf16_t>(sh, Q, K, row_lse, mass, lse, st);
+    case KVM_F32: {
+        kvm_status rc = launch_t<float>(sh, Q, K, row_lse, mass, lse, nullptr, st);
+        return rc == KVM_OK && sim_opt ? launch_cosine_scan(sh, K, sim_opt, st) : rc;
+    }
+    case KVM_F16: return launch_t<half_t>(sh, Q, K, row_lse, mass, lse, sim_opt, st);
+    default: return launch_t<bf16_t>(sh, Q, K, row_lse, mass, lse, sim_opt, st);
     }
 }
 

@@ -231,8 +231,8 @@ __device__ __forceinline__ void colsum_diag_dispatch(int nf, bool masked, const 
 template <typename T>
 __global__ __launch_bounds__(ATT_BLOCK, PIPE_WGS_PER_CU) void attn_colsum_pipe_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const float *__restrict__ neg_lse, float *__restrict__ mass,
-    const int32_t *__restrict__ seq_lens, int n_kvslices, int H, int G, int N, int n_pad, int tiles_per_slice,
-    int wgs_per_slice, float c)
+    float *__restrict__ sim_opt, const int32_t *__restrict__ seq_lens, int n_kvslices, int H, int G, int N, int n_pad,
+    int tiles_per_slice, int wgs_per_slice, float c)
 {
     using TL = Tile<T>;
     constexpr int TR = TL::TR;                                // 64 rows per streamed tile
@@ -250,6 +250,7 @@ __global__ __launch_bounds__(ATT_BLOCK, PIPE_WGS_PER_CU) void attn_colsum_pipe_k
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float *mass_s = mass + (size_t)kvslice * N;
+    float *sim_s = sim_opt ? sim_opt + (size_t)kvslice * N : nullptr;
     const T *Ks = K + (size_t)kvslice * N * HEAD_DIM;
     const int slot0 = frag_slot0(lane);
     int blk_of[PIPE_R];                                       // the wave's blocks, ascending (scalar)
@@ -264,7 +265,10 @@ __global__ __launch_bounds__(ATT_BLOCK, PIPE_WGS_PER_CU) void attn_colsum_pipe_k
     if (pass == 1 && (!paired || tm.tile >= tiles_per_slice - 1 - tm.tile)) break;
     const int k_begin = tile * PIPE_ROWS;
     if (k_begin >= n) {                                       // padding only: defined zeros
-        for (int j = k_begin + threadIdx.x; j < min(k_begin + PIPE_ROWS, N); j += ATT_BLOCK) mass_s[j] = 0.f;
+        for (int j = k_begin + threadIdx.x; j < min(k_begin + PIPE_ROWS, N); j += ATT_BLOCK) {
+            mass_s[j] = 0.f;
+            if (sim_s) sim_s[j] = 0.f;
+        }
         continue;
     }
     // Query tiles first .. last see these keys; tiles first .. first+7 hold the diagonal.  They are
@@ -290,6 +294,13 @@ __global__ __launch_bounds__(ATT_BLOCK, PIPE_WGS_PER_CU) void attn_colsum_pipe_k
     u32x4 kf[PIPE_R][8];
 #pragma unroll
     for (int i = 0; i < PIPE_R; ++i) load_stationary<T>(Ks, k_begin + 32 * blk_of[i], n, lane, kf[i]);
+    if (sim_s) {                                              // the keys are here anyway: their adjacent similarities
+        u32x4 before[PIPE_R];
+#pragma unroll
+        for (int i = 0; i < PIPE_R; ++i) before[i] = load_predecessor<T>(Ks, k_begin + 32 * blk_of[i], n, lane);
+#pragma unroll
+        for (int i = 0; i < PIPE_R; ++i) stationary_cosine<T>(k_begin + 32 * blk_of[i], n, N, lane, kf[i], before[i], sim_s);
+    }
     float part[PIPE_R];
 #pragma unroll
     for (int i = 0; i < PIPE_R; ++i) part[i] = 0.f;
@@ -374,22 +385,22 @@ __global__ __launch_bounds__(ATT_BLOCK, PIPE_WGS_PER_CU) void attn_colsum_pipe_k
 // ------------------------------------------------------------------------------------------
 
 template <typename T>
-static void launch_colsum_pipe_t(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass, int n_pad,
-                                 float c, hipStream_t st)
+static void launch_colsum_pipe_t(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass,
+                                 float *sim_opt, int n_pad, float c, hipStream_t st)
 {
     const int tiles = (sh.N + PIPE_ROWS - 1) / PIPE_ROWS;
     const int wgs = tiles >= PIPE_PAIR_MIN_TILES ? (tiles + 1) / 2 : tiles;
     const int n_kv = sh.B * sh.H_kv;
     const long long blocks = (long long)((n_kv + 7) / 8) * 8 * wgs;
     hipLaunchKernelGGL(attn_colsum_pipe_kernel<T>, dim3((unsigned)blocks), dim3(ATT_BLOCK), 0, st, (const T *)Q, (const T *)K,
-                       neg_lse, mass, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, wgs, c);
+                       neg_lse, mass, sim_opt, sh.seq_lens, n_kv, sh.H_kv, sh.G, sh.N, n_pad, tiles, wgs, c);
 }
 
-void launch_colsum_pipe(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass, int n_pad, float c,
-                        hipStream_t st)
+void launch_colsum_pipe(const kvm_shape &sh, const void *Q, const void *K, const float *neg_lse, float *mass, float *sim_opt,
+                        int n_pad, float c, hipStream_t st)
 {
-    if (sh.dtype == KVM_F16) launch_colsum_pipe_t<half_t>(sh, Q, K, neg_lse, mass, n_pad, c, st);
-    else launch_colsum_pipe_t<bf16_t>(sh, Q, K, neg_lse, mass, n_pad, c, st);
+    if (sh.dtype == KVM_F16) launch_colsum_pipe_t<half_t>(sh, Q, K, neg_lse, mass, sim_opt, n_pad, c, st);
+    else launch_colsum_pipe_t<bf16_t>(sh, Q, K, neg_lse, mass, sim_opt, n_pad, c, st);
 }
 
 }  // namespace kvm

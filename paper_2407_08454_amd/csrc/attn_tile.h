@@ -142,6 +142,53 @@ __device__ __forceinline__ void load_stationary(const T *base, int row0, int n_v
     }
 }
 
+// Cosine similarity of adjacent keys (Section 3.1 Eq. (2)) from a stationary block of keys that a
+// column-sum kernel holds in registers anyway: sim[j] = cos(k_{j-1}, k_j) for the 32 rows from row0
+// on (0 for j = 0, for a zero-norm key and on padding), the values cosine_scan_kernel writes, up to
+// the order of the fp32 additions.  Lanes l and l+32 hold the even and the odd 16-byte chunks of
+// row l; the row before is one lane below, except for the block's first row, whose predecessor
+// comes from memory (load_predecessor).  16-bit types only.
+// The predecessor of a block's first row: one 16-byte chunk per lane of the first 16 (issued with
+// the loads of the stationary operand, used by stationary_cosine).
+template <typename T>
+__device__ __forceinline__ u32x4 load_predecessor(const T *Ks, int row0, int n, int lane)
+{
+    u32x4 chunk = {0u, 0u, 0u, 0u};
+    if (lane < 16 && row0 >= 1 && row0 < n)
+        chunk = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(Ks + (size_t)(row0 - 1) * HEAD_DIM) + lane * 16);
+    return chunk;
+}
+
+template <typename T>
+__device__ __forceinline__ void stationary_cosine(int row0, int n, int N, int lane, const u32x4 *frags, const u32x4 &chunk,
+                                                  float *sim_s)
+{
+    typedef typename Elem<T>::Raw Raw;
+    const int row = row0 + (lane & 31);
+    const bool first = (lane & 31) == 0;                     // lanes 0 and 32 collect the even and the odd chunks
+    float dot = 0.f, nn = 0.f, pn = 0.f;
+#pragma unroll
+    for (int f = 0; f < Mma<T>::FRAGS; ++f) {
+        u32x4 prev, far;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            prev[i] = (uint32_t)__shfl_up((int)frags[f][i], 1, WAVE);
+            far[i] = (uint32_t)__shfl((int)chunk[i], 2 * f + (lane >> 5), WAVE);
+        }
+        if (first) prev = far;
+        pn += RowDot<T>::dot(Raw{far}, Raw{far});             // (used by the first lanes only)
+        dot += RowDot<T>::dot(Raw{frags[f]}, Raw{prev});
+        nn += RowDot<T>::dot(Raw{frags[f]}, Raw{frags[f]});
+    }
+    dot += __shfl_xor(dot, 32, WAVE);
+    nn += __shfl_xor(nn, 32, WAVE);
+    pn += __shfl_xor(pn, 32, WAVE);
+    float nn_prev = __shfl_up(nn, 1, WAVE);
+    if (first) nn_prev = pn;
+    const float s = (row >= 1 && row < n) ? (dot * inv_norm(nn)) * inv_norm(nn_prev) : 0.f;
+    if (lane < 32 && row < N) sim_s[row] = s;
+}
+
 // blockIdx -> (slice, tile).  Workgroups are dealt round-robin to the 8 XCDs, each with its
 // own L2: all tiles of a slice go to one XCD so that the slice's K and Q are fetched once.
 // Within a slice the tiles with the most causal work come first.

@@ -25,9 +25,6 @@ constexpr int COS_ROWS_PER_GROUP = 16;                      // consecutive rows 
 constexpr int COS_ROWS_PER_BLOCK = COS_GROUPS * COS_ROWS_PER_GROUP;
 
 
-// 1/sqrt(x) for a squared norm; 0 when the squared norm is zero or below the normal fp32 range
-// (such a key counts as a zero-norm key: its similarities are 0)
-__device__ __forceinline__ float inv_norm(float nn) { return nn >= 1.17549435e-38f ? __builtin_amdgcn_rsqf(nn) : 0.f; }
 
 template <typename T>
 __global__ __launch_bounds__(COS_BLOCK) void cosine_scan_kernel(const T *__restrict__ K, float *__restrict__ sim,
@@ -1172,6 +1169,18 @@ kvm_status launch_sim_append(const kvm_shape &sh, const void *K, float *sim, hip
     default: hipLaunchKernelGGL(sim_append_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)K, sim, sh.seq_lens, sh.H_kv, sh.N, (int)slices); break;
     }
     return check_launch("sim_append_kernel");
+}
+
+// The scan alone (for callers inside the library that want the similarities without the sets).
+kvm_status launch_cosine_scan(const kvm_shape &sh, const void *K, float *sim, hipStream_t st)
+{
+    if ((long long)sh.B * sh.H_kv == 0 || sh.N == 0) return KVM_OK;
+    switch (sh.dtype) {
+    case KVM_F32: launch_cosine<float>(sh, K, sim, nullptr, st); break;
+    case KVM_F16: launch_cosine<half_t>(sh, K, sim, nullptr, st); break;
+    default: launch_cosine<bf16_t>(sh, K, sim, nullptr, st); break;
+    }
+    return check_launch("cosine_scan_kernel");
 }
 
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K, const float *mass,

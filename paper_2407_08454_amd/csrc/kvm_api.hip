@@ -186,7 +186,8 @@ size_t kvm_workspace_bytes(const kvm_shape *shape, const kvm_params *params)
 }
 
 static kvm_status attn_mass_entry(const char *who, const kvm_shape *shape, const void *Q, const void *K, const float *row_lse,
-                                  bool with_lse, float *mass, void *ws, size_t ws_bytes, void *stream)
+                                  bool with_lse, float *mass, float *sim, bool with_sim, void *ws, size_t ws_bytes,
+                                  void *stream)
 {
     kvm_status rc = check_shape(shape, who);
     if (rc != KVM_OK) return rc;
@@ -195,24 +196,35 @@ static kvm_status attn_mass_entry(const char *who, const kvm_shape *shape, const
         set_error("%s: Q, K%s and mass must not be NULL", who, with_lse ? ", row_lse" : "");
         return KVM_ERR_INVALID_ARG;
     }
+    if (!empty && with_sim && !sim) {
+        set_error("%s: sim must not be NULL", who);
+        return KVM_ERR_INVALID_ARG;
+    }
     if (empty) return KVM_OK;
     if (!ws || ws_bytes < ws_attn(shape)) {
         set_error("%s: workspace of %zu bytes needed, %zu given", who, ws_attn(shape), ws ? ws_bytes : (size_t)0);
         return KVM_ERR_WORKSPACE;
     }
-    return launch_attn_mass(*shape, Q, K, with_lse ? row_lse : nullptr, mass, (float *)ws, (hipStream_t)stream);
+    return launch_attn_mass(*shape, Q, K, with_lse ? row_lse : nullptr, mass, (float *)ws, with_sim ? sim : nullptr,
+                            (hipStream_t)stream);
 }
 
 kvm_status kvm_attn_mass(const kvm_shape *shape, const void *Q, const void *K, float *mass, void *ws, size_t ws_bytes,
                          void *stream)
 {
-    return attn_mass_entry("kvm_attn_mass", shape, Q, K, nullptr, false, mass, ws, ws_bytes, stream);
+    return attn_mass_entry("kvm_attn_mass", shape, Q, K, nullptr, false, mass, nullptr, false, ws, ws_bytes, stream);
+}
+
+kvm_status kvm_attn_mass_sim(const kvm_shape *shape, const void *Q, const void *K, float *mass, float *sim, void *ws,
+                             size_t ws_bytes, void *stream)
+{
+    return attn_mass_entry("kvm_attn_mass_sim", shape, Q, K, nullptr, false, mass, sim, true, ws, ws_bytes, stream);
 }
 
 kvm_status kvm_attn_mass_from_lse(const kvm_shape *shape, const void *Q, const void *K, const float *row_lse, float *mass,
                                   void *ws, size_t ws_bytes, void *stream)
 {
-    return attn_mass_entry("kvm_attn_mass_from_lse", shape, Q, K, row_lse, true, mass, ws, ws_bytes, stream);
+    return attn_mass_entry("kvm_attn_mass_from_lse", shape, Q, K, row_lse, true, mass, nullptr, false, ws, ws_bytes, stream);
 }
 
 kvm_status kvm_attn_mass_append(const kvm_shape *shape, const void *q_new, const void *K, float *mass, void *ws,

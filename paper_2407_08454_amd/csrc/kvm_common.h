@@ -135,6 +135,10 @@ template <> struct RowDot<float> {
     }
 };
 
+// 1/sqrt(x) for a squared norm; 0 when the squared norm is zero or below the normal fp32 range
+// (such a key counts as a zero-norm key: its similarities are 0)
+__device__ __forceinline__ float inv_norm(float nn) { return nn >= 1.17549435e-38f ? __builtin_amdgcn_rsqf(nn) : 0.f; }
+
 // ---- cross-lane helpers -------------------------------------------------------------
 
 // DPP move within a row of 16 lanes; every lane is enabled so no old value is needed.
@@ -183,7 +187,8 @@ struct ProfScope {
 };
 
 kvm_status launch_attn_mass(const kvm_shape &sh, const void *Q, const void *K, const float *row_lse, float *mass,
-                            float *lse, hipStream_t st);
+                            float *lse, float *sim_opt, hipStream_t st);
+kvm_status launch_cosine_scan(const kvm_shape &sh, const void *K, float *sim, hipStream_t st);
 kvm_status launch_attn_append(const kvm_shape &sh, const void *q_new, const void *K, float *mass, float *ws, hipStream_t st);
 kvm_status launch_sim_append(const kvm_shape &sh, const void *K, float *sim, hipStream_t st);
 kvm_status launch_identify(const kvm_shape &sh, const kvm_params &pr, int cap_rows, const void *K,

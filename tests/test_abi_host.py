@@ -110,6 +110,14 @@ def test_host_detectable_errors_return_before_any_launch():
     assert attn_lse(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"kvm_attn_mass_from_lse" in lib.kvm_last_error()
     assert attn_lse(_shape(N=0), row_lse=None, ws=None) == kb.KVM_OK          # nothing to do
 
+    def attn_sim(sh, sim=one, ws=one, nbytes=1 << 30):
+        return lib.kvm_attn_mass_sim(ctypes.byref(sh), one, one, one, sim, ws, nbytes, None)
+
+    assert attn_sim(_shape(d=64)) == kb.KVM_ERR_UNSUPPORTED
+    assert attn_sim(_shape(), sim=None) == kb.KVM_ERR_INVALID_ARG and b"sim" in lib.kvm_last_error()
+    assert attn_sim(_shape(), nbytes=16) == kb.KVM_ERR_WORKSPACE and b"kvm_attn_mass_sim" in lib.kvm_last_error()
+    assert attn_sim(_shape(N=0), sim=None, ws=None) == kb.KVM_OK              # nothing to do
+
     def append(sh, q=one, ws=one, nbytes=1 << 30):
         return lib.kvm_attn_mass_append(ctypes.byref(sh), q, one, one, ws, nbytes, None)
 

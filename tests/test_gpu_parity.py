@@ -45,6 +45,58 @@ def _slices(seed, B, H, n_list, N, d, G, dtype, rho=None):
 
 
 # ---------------------------------------------------------------------------------------------
+# similarities out of the score pass (kvm_attn_mass_sim)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,N,lens,G", [("f16", 700, [700, 333, 0], 2), ("bf16", 700, [641, 700, 1], 1),
+                                            ("f32", 300, [300, 77, 0], 2), ("f16", 8200, [8200, 5000, 513], 1),
+                                            ("bf16", 8704, [8704, 8193, 64], 2)])
+def test_attn_mass_sim_gives_the_scan_s_similarities(dtype, N, lens, G):
+    """The column-sum kernels also write the adjacent-key cosines (two-block kernel below 8192 tokens, four-block
+    kernel from there on, the streaming scan for fp32): against the oracle's similarities to the bar of the scan,
+    zero at token 0, on padding and around a zero-norm key; the scores bit for bit those of kvm_attn_mass; and the
+    sets identified from these similarities are the oracle's."""
+    _say(f"mass + similarities in one pass: {dtype} N={N} lens={lens} G={G}")
+    B, H = len(lens), 2
+    Q, K, V = _slices(51, B, H, lens, N, 128, G, dtype)
+    K[0, 1, 40] = 0                                          # a zero-norm key: similarity 0 to both neighbours
+    K[0, 0, 31:34] = K[0, 0, 31]                             # identical keys across a 32-row block edge: similarity 1
+    Qd, Kd = gu.to_dev(Q, dtype), gu.to_dev(K, dtype)
+    sh = kb.make_shape(Kd, G, gu.lens_dev(lens))
+    params = kb.kvm_params_for_budget(0.5)
+    ws = torch.empty(max(kb.kvm_workspace_bytes(sh, params), 256), dtype=torch.uint8, device="cuda")
+    mass = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    mass2 = torch.full_like(mass, float("nan"))
+    sim = torch.full_like(mass, float("nan"))
+    kb.kvm_attn_mass(sh, Qd, Kd, mass, ws)
+    kb.kvm_attn_mass_sim(sh, Qd, Kd, mass2, sim, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(mass.view(torch.int32), mass2.view(torch.int32))
+    m32 = mass.cpu().numpy()
+    o = ref.identify_sets(K, m32.astype(np.float64), dtype, params.budget, params.recent_ratio, params.heavy_ratio,
+                          params.threshold, True, kb.kvm_out_capacity(sh, params), lens)
+    o["cap_rows"] = kb.kvm_out_capacity(sh, params)
+    g_sim = sim.cpu().numpy()
+    np.testing.assert_allclose(g_sim, o["sim"], atol=2e-6)
+    for b, n in enumerate(lens):
+        assert (g_sim[b, :, n:] == 0).all() and (n == 0 or (g_sim[b, :, 0] == 0).all())
+    assert g_sim[0, 1, 40] == 0 and g_sim[0, 1, 41] == 0
+    assert abs(g_sim[0, 0, 32] - 1) <= 2e-6 and abs(g_sim[0, 0, 33] - 1) <= 2e-6
+    # sets from these similarities
+    given = kb.KvmParams.from_buffer_copy(params)
+    given.sim_given = 1
+    cap = kb.kvm_out_capacity(sh, params)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    out = dict(set_id=torch.full((B, H, N), -7, **i32), set_start=torch.full((B, H, cap + 1), -7, **i32),
+               pivot=torch.full((B, H, cap), -7, **i32), n_sets=torch.full((B, H), -7, **i32), status=torch.full((B, H), -7, **i32))
+    kb.kvm_identify_sets(sh, given, Kd, mass, out["set_id"], out["set_start"], out["pivot"], out["n_sets"], sim, out["status"], ws)
+    torch.cuda.synchronize()
+    g = {k: v.cpu().numpy() for k, v in out.items()}
+    excused, near = gu.compare_maps(g, o, lens, N, params.threshold, "sets from the score pass's similarities")
+    _say(f"  slices excused by a similarity at the threshold: {excused} (near-threshold similarities: {near})")
+
+
+# ---------------------------------------------------------------------------------------------
 # (a) aggregated attention mass
 # ---------------------------------------------------------------------------------------------
 
@@ -836,14 +888,16 @@ def _explained_by_near_ties_in_mass(m_o, oi, og, ge, n, what):
     return "pivot near-tie"
 
 
-def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what, device_tensors=None, slice_of=None):
+def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what, device_tensors=None, slice_of=None,
+                sim_from_score_pass=False):
     """GPU: the three calls back to back on all slices.  Oracle: the same on sampled slices.
     Stage by stage the oracle's inputs are its own.  End to end the library's maps must be exactly
     what the oracle's rule gives on the library's own fp32 scores (themselves checked against the
     oracle's scores first), the only excuse being a similarity within 1e-6 of the threshold; where
     they differ from the oracle's maps on the oracle's scores the deciding scores must be a near-tie.
     With device_tensors = (Qd, Kd, Vd) the inputs are already on the GPU and slice_of(b, h) returns
-    the host copy (Q (G, N, d), K (N, d), V (N, d)) of a sampled slice."""
+    the host copy (Q (G, N, d), K (N, d), V (N, d)) of a sampled slice.  sim_from_score_pass: the
+    similarities come from kvm_attn_mass_sim instead of the sets' own scan of K."""
     if device_tensors is None:
         Qd, Kd, Vd = gu.to_dev(Q, dtype), gu.to_dev(K, dtype), gu.to_dev(V, dtype)
         slice_of = lambda b, h: (Q[b, h * G:(h + 1) * G], K[b, h], V[b, h])
@@ -852,7 +906,7 @@ def _whole_pass(Q, K, V, dtype, G, params, lens, sample, what, device_tensors=No
     sl = gu.lens_dev(lens)
     sh = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(sh, params, "cuda", gu.TORCH_DT[dtype], with_debug=True)
-    kb.compress(sh, params, Qd, Kd, Vd, buf)
+    kb.compress(sh, params, Qd, Kd, Vd, buf, sim_from_score_pass=sim_from_score_pass)
     torch.cuda.synchronize()
     B, H, N, d = Kd.shape
     g = dict(set_id=buf.set_id.cpu().numpy(), set_start=buf.set_start.cpu().numpy(), pivot=buf.pivot.cpu().numpy(),
@@ -950,6 +1004,21 @@ def test_whole_pass_config4_grouped_queries_long():
     _say("whole pass: config 4 shape (G=4, N=16384), one layer")
     Q, K, V, lens = synth.gen_config(cfg, layers=1)
     g = _whole_pass(Q, K, V, "bf16", 4, kb.kvm_params_for_budget(0.5), None, [(0, 3)], "config 4")
+    # the same pass with the similarities written by the four-block column-sum kernel: the same maps, unless a
+    # similarity sits within the two paths' rounding of the threshold
+    params = kb.kvm_params_for_budget(0.5)
+    Qd, Kd, Vd = gu.to_dev(Q, "bf16"), gu.to_dev(K, "bf16"), gu.to_dev(V, "bf16")
+    sh = kb.make_shape(Kd, 4, None)
+    bufs = [kb.Buffers(sh, params, "cuda", torch.bfloat16, with_sim=True) for _ in range(2)]
+    kb.compress(sh, params, Qd, Kd, Vd, bufs[0])
+    kb.compress(sh, params, Qd, Kd, Vd, bufs[1], sim_from_score_pass=True)
+    torch.cuda.synchronize()
+    assert torch.equal(bufs[0].mass, bufs[1].mass)
+    np.testing.assert_allclose(bufs[1].sim.cpu().numpy(), bufs[0].sim.cpu().numpy(), atol=2e-6)
+    for h in range(8):
+        same = all(torch.equal(getattr(bufs[0], k)[0, h], getattr(bufs[1], k)[0, h]) for k in ("set_id", "set_start", "pivot", "n_sets"))
+        near = (bufs[0].sim[0, h, 1:] - params.threshold).abs().min().item() <= 2e-6
+        assert same or near, f"head {h}: maps differ between the two ways to get the similarities"
     assert (g["n_sets"] <= 8192).all()
 
 
@@ -1080,7 +1149,7 @@ def test_whole_pass_random_shapes(case):
          f"weights={params.weights} pivot={params.pivot_rule} sets={params.set_rule} eps={params.threshold}")
     Q, K, V = _slices(2000 + case, B, H, lens, N, 128, G, dtype)
     sample = [(b, h) for b in range(B) for h in range(H)]
-    _whole_pass(Q, K, V, dtype, G, params, lens, sample, f"random shapes {case}")
+    _whole_pass(Q, K, V, dtype, G, params, lens, sample, f"random shapes {case}", sim_from_score_pass=case % 2 == 1)
 
 
 # ---------------------------------------------------------------------------------------------
