@@ -6,6 +6,7 @@ import math
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2407_08454_amd import binding as kb
@@ -200,3 +201,18 @@ def test_binding_refuses_mismatched_tensors_on_the_host():
         kb.make_shape(K.to(torch.float64))
     with pytest.raises(ValueError):                       # CPU tensors never reach the library
         kb.kvm_attn_mass(sh, K, K, torch.zeros((1, 2, 8)), torch.zeros(1024, dtype=torch.uint8))
+
+
+def test_layer_by_layer_generation_gives_the_bits_of_the_whole_workload():
+    """Large workloads are generated one layer at a time on the host; the layers must be the ones
+    the whole-workload generator gives (same seeds per slice)."""
+    from paper_2407_08454_amd import synth
+    cfg = dict(name="tiny", layers=3, batch=2, H_kv=2, G=2, N=64, d=128, dtype="bf16", rho=None, budgets=(0.5,), seed=7,
+               seq_lens=(40, 64))
+    Q, K, V, sl = synth.gen_config(cfg, workers=1)
+    layers = list(synth.gen_config_layers(cfg, workers=1))
+    assert len(layers) == 3
+    for layer, (q, k, v, s) in enumerate(layers):
+        rows = slice(layer * 2, layer * 2 + 2)                   # layers are folded into the batch axis
+        assert np.array_equal(q, Q[rows]) and np.array_equal(k, K[rows]) and np.array_equal(v, V[rows])
+        assert np.array_equal(s, sl[rows])
