@@ -1187,6 +1187,110 @@ def test_evict_matches_the_oracle(dtype):
                 assert (gk[b, h, m:] == 0).all()              # rows beyond the kept ones are not written
 
 
+def _random_partition(rng, n, p_boundary, long_run=None):
+    """Set starts and pivots of a random contiguous partition of n tokens."""
+    if n == 0:
+        return np.zeros(0, np.int64), np.zeros(0, np.int64)
+    is_start = rng.random(n) < p_boundary
+    is_start[0] = True
+    if long_run is not None:
+        is_start[long_run[0] + 1:long_run[1]] = False
+    starts = np.flatnonzero(is_start)
+    ends = np.append(starts[1:], n)
+    return starts, starts + (rng.random(len(starts)) * (ends - starts)).astype(np.int64)
+
+
+def _maps_of(starts_list, pivots_list, lens, N, cap):
+    S = len(starts_list)
+    sid = np.full((S, N), -1, np.int32)
+    sst = np.zeros((S, cap + 1), np.int32)
+    pv = np.full((S, cap), -1, np.int32)
+    ns = np.zeros(S, np.int32)
+    for i, (starts, piv) in enumerate(zip(starts_list, pivots_list)):
+        M = len(starts)
+        ns[i] = M
+        sst[i, :M], sst[i, M:], pv[i, :M] = starts, lens[i], piv
+        for s, (a, b) in enumerate(zip(starts, list(starts[1:]) + [lens[i]])):
+            sid[i, a:b] = s
+    return sid, sst, pv, ns
+
+
+def test_merge_refresh_random_map_changes():
+    """Hand-made pairs of valid maps (not from kvm_identify_sets): random partitions, then boundaries toggled
+    anywhere, pivots changed, a few tokens appended, sets of more than 512 tokens among them, so that rows move
+    up and down in one call and the set count changes by more than one.  kvm_merge_refresh on the cache of the
+    old maps must give the bits of kvm_merge on the new maps.  (A longer run of this generator, 15000 cases,
+    was clean.)"""
+    rng = np.random.default_rng(77)
+    for case in range(120):
+        dtype = ["f16", "bf16", "f32"][case % 3]
+        N = int(rng.choice([3, 64, 300, 1000, 1537, 3000]))
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        S = B * H
+        grow = int(rng.integers(0, 3))
+        new_b = [int(rng.integers(max(1, N // 2), N + 1)) for _ in range(B)]
+        old_b = [max(0, n - grow) for n in new_b]
+        lens_new, lens_old = [new_b[i // H] for i in range(S)], [old_b[i // H] for i in range(S)]
+        params = kb.make_params(1.0, 0.0, 0.0, enforce_budget=False)
+        if case % 4 == 1:
+            params.sigma_mode, params.sigma = kb.KVM_SIGMA_FIXED, 3.0
+        if case % 4 == 2:
+            params.weights = kb.KVM_WEIGHTS_AVERAGE
+        if case % 20 == 0:
+            _say(f"merge refresh on random map changes: case {case}, {dtype}, N={N}, {S} slices")
+        K = synth.to_storage(rng.standard_normal((B, H, N, 128), dtype=np.float32), dtype)
+        V = synth.to_storage(rng.standard_normal((B, H, N, 128), dtype=np.float32), dtype)
+        Kd, Vd = gu.to_dev(K, dtype), gu.to_dev(V, dtype)
+        cap, p_boundary = N, float(rng.choice([0.02, 0.2, 0.6]))
+        o_st, o_pv, n_st, n_pv = [], [], [], []
+        for i in range(S):
+            n0, n1 = lens_old[i], lens_new[i]
+            long_run = None
+            if n0 > 700 and rng.random() < 0.4:
+                a = int(rng.integers(0, n0 - 600))
+                long_run = (a, a + int(rng.integers(520, 600)))
+            st, pv = _random_partition(rng, n0, p_boundary, long_run)
+            o_st.append(st), o_pv.append(pv)
+            is_start = np.zeros(n1, bool)
+            is_start[st] = True
+            for _ in range(int(rng.integers(0, 6))):
+                j = int(rng.integers(1, max(2, n1)))
+                if j < n1:
+                    is_start[j] = ~is_start[j]
+            if n1 > n0:
+                is_start[n0:n1] = rng.random(n1 - n0) < 0.7
+            is_start[0] = True
+            st2 = np.flatnonzero(is_start)
+            en2 = np.append(st2[1:], n1)
+            old_piv = {int(a): int(q) for a, q in zip(st, pv)}
+            old_end = {int(a): int(b) for a, b in zip(st, np.append(st[1:], n0))}
+            pv2 = np.empty(len(st2), np.int64)
+            for s_, (a, b) in enumerate(zip(st2, en2)):
+                keep = int(a) in old_piv and old_end[int(a)] == int(b) and rng.random() < 0.95
+                pv2[s_] = old_piv[int(a)] if keep else a + int(rng.random() * (b - a))
+            n_st.append(st2), n_pv.append(pv2)
+        old = _maps_of(o_st, o_pv, lens_old, N, cap)
+        new = _maps_of(n_st, n_pv, lens_new, N, cap)
+        shapes = ((B, H, N), (B, H, cap + 1), (B, H, cap), (B, H))
+        d_old = [torch.from_numpy(a.reshape(shp)).cuda() for a, shp in zip(old, shapes)]
+        d_new = [torch.from_numpy(a.reshape(shp)).cuda() for a, shp in zip(new, shapes)]
+        sh_old, sh_new = kb.make_shape(Kd, 1, gu.lens_dev(old_b)), kb.make_shape(Kd, 1, gu.lens_dev(new_b))
+        ws = torch.empty(max(kb.kvm_workspace_bytes(sh_new, params), 256), dtype=torch.uint8, device="cuda")
+        Ko = torch.zeros((B, H, cap, 128), dtype=gu.TORCH_DT[dtype], device="cuda")
+        Vo, Kf, Vf = torch.zeros_like(Ko), torch.zeros_like(Ko), torch.zeros_like(Ko)
+        kb.kvm_merge(sh_old, params, Kd, Vd, d_old[1], d_old[2], d_old[3], Ko, Vo, None, ws)
+        kb.kvm_merge_refresh(sh_new, params, Kd, Vd, *d_old, d_new[1], d_new[2], d_new[3], Ko, Vo, None, ws)
+        kb.kvm_merge(sh_new, params, Kd, Vd, d_new[1], d_new[2], d_new[3], Kf, Vf, None, ws)
+        torch.cuda.synchronize()
+        bits = torch.int32 if dtype == "f32" else torch.int16
+        for i in range(S):
+            b, h = divmod(i, H)
+            M = int(new[3][i])
+            assert torch.equal(Ko[b, h, :M].view(bits), Kf[b, h, :M].view(bits)) and \
+                torch.equal(Vo[b, h, :M].view(bits), Vf[b, h, :M].view(bits)), \
+                f"case {case} ({dtype}, N={N}) slice {i}: refreshed rows differ from a full merge (M {int(old[3][i])} -> {M})"
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 def test_evict_merge_values_matches_the_oracle(dtype):
     """Value-only merging (comparison workload): kept positions and keys bit-exact, the averaged values
