@@ -71,6 +71,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload id (2 = the headline Llama2-7B shape)")
     ap.add_argument("--layers", type=int, default=None, help="generate only this many layers (not the headline run)")
     ap.add_argument("--budget", type=float, default=0.5)
+    ap.add_argument("--threshold", type=float, default=None, help="similarity threshold (default: the preset's 0.75)")
     ap.add_argument("--cpu-slices", type=int, default=512, help="slices the oracle is timed on (0 = skip)")
     ap.add_argument("--sim-from-score-pass", action="store_true",
                     help="similarities written by the score pass (kvm_attn_mass_sim) instead of kvm_identify_sets' own scan of K")
@@ -131,6 +132,8 @@ def main() -> int:
     Qd, Kd, Vd = dev(Q), dev(K), dev(V)
     sl = None if lens is None else torch.from_numpy(lens).cuda()
     params = kb.kvm_params_for_budget(args.budget)
+    if args.threshold is not None:
+        params.threshold = args.threshold
     params.weights = {"gaussian": kb.KVM_WEIGHTS_GAUSSIAN, "average": kb.KVM_WEIGHTS_AVERAGE}[args.weights]
     params.pivot_rule = {"max-score": kb.KVM_PIVOT_MAX_SCORE, "last": kb.KVM_PIVOT_LAST,
                          "random": kb.KVM_PIVOT_RANDOM}[args.pivot]
@@ -139,7 +142,8 @@ def main() -> int:
     if args.sets == "anchor":
         params.set_rule = kb.KVM_SETS_ANCHOR
     variant = (f"sets {args.sets}, weights {args.weights}, pivot {args.pivot}, "
-               f"sigma {'per set' if args.sigma is None else args.sigma}")
+               f"sigma {'per set' if args.sigma is None else args.sigma}"
+               + ("" if args.threshold is None else f", threshold {args.threshold}"))
     shape = kb.make_shape(Kd, G, sl)
     buf = kb.Buffers(shape, params, "cuda", tdt, with_sim=args.sim_from_score_pass)
 
@@ -286,7 +290,7 @@ def main() -> int:
     if args.keys == "identical":
         variant += "; identical keys (one merging set per slice)"
     headline = (args.keys == "ar1" and args.config == 2 and args.layers is None and args.budget == 0.5 and args.weights == "gaussian"
-                and args.pivot == "max-score" and args.sigma is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None and not fused)
+                and args.pivot == "max-score" and args.sigma is None and args.threshold is None and args.sets == "adjacent" and args.method == "merge" and row_lse is None and not fused)
 
     counters = measured_traffic("llama2-7b_n4096_f16") if headline else {}
 
