@@ -11,6 +11,12 @@
 //                       radix select, boundary flags, prefix scan to set ids, the budget
 //                       fallback, and a segmented arg-max scan for the pivots.  All integer
 //                       outputs are deterministic.
+//   segment_reg_kernel  the same for the adjacent rule and up to 16384 tokens with the slice held
+//                       in registers (16 tokens per thread)
+//   sim_append_kernel   decode time: the one new similarity
+//   evict_select_kernel, gather_rows_kernel, gather_merge_values_kernel
+//                       comparison workloads (eviction by score; evicted values averaged into the
+//                       nearest kept token)
 #include "kvm_common.h"
 
 namespace kvm {

@@ -11,6 +11,16 @@
 // fp32, then one rounded row is written per output.  Loads are issued 16 rows at a time; a
 // set of up to 16 tokens is read exactly once and held in registers.  Runs of singleton sets
 // are copied bit for bit.  HBM traffic: K once, V once, 2 M rows out.
+//
+// Kernels:
+//   merge_plan_kernel   per slice: first set of every 64-token tile, and the list of sets of more
+//                       than LONG_SET_MIN tokens
+//   merge_kernel        one wave per tile (merge_one_set per set, runs of singletons copied)
+//   merge_long_kernel   the listed long sets, one 1024-thread workgroup per slice
+//   refresh_kernel      decode time: compares the new maps with the previous ones, moves the rows of
+//                       unchanged sets in place and merges the changed sets again
+// and the launcher that keeps the plan in a file-scope device array for callers that cannot
+// bring a workspace (kvm_merge_static).
 #include <mutex>
 
 #include "kvm_common.h"
